@@ -1,0 +1,171 @@
+/*
+ * spec_verify.h - C ABI of the batched speculative-verification step for
+ * AMD Instinct MI355X (gfx950).
+ *
+ * The step is the data-parallel hot path behind goodput-driven speculation
+ * control (arXiv 2406.14066): for B requests, request b having k_b draft
+ * tokens and a paged KV cache of kv_len[b] tokens,
+ *   (a) "score": lookahead attention of the k_b+1 query positions against the
+ *       request's KV cache, causal inside the draft (Section 2.2: position
+ *       n+i is conditioned on x_1..x_{n+i-1}; Section 4: all k+1 positions are
+ *       scored in one forward pass; Eq. 3 attributes the context-dependent
+ *       part of that pass to loading the KV cache), and
+ *   (b) "accept": rejection sampling over the vocabulary (Section 4's
+ *       acceptance phase), giving the number m_b of accepted draft tokens and
+ *       the bonus token that corrects the first wrong draft token or extends a
+ *       fully accepted draft, so the step emits m_b+1 tokens (Section 2.2),
+ *       plus the counters behind goodput (Eq. 1) and the acceptance-rate
+ *       estimate that feeds Eq. 4.
+ *
+ * Conventions
+ *   - Pointers are DEVICE pointers unless the name starts with host_.
+ *   - Ownership: the library allocates and frees nothing.  The caller owns all
+ *     buffers and the workspace, and keeps them valid until the stream has
+ *     finished the call.
+ *   - Calls enqueue work on `hip_stream` (a hipStream_t; NULL = the default
+ *     stream) and return without synchronising.
+ *   - Arguments are validated on the host before anything is launched; a
+ *     failed validation launches nothing.  A launch failure is SPEC_EHIP.
+ *   - Same inputs and same (philox_seed, philox_step) give the same outputs.
+ *   - Limits: k_b <= SPEC_K_MAX, block_size == 16, d in {64, 128},
+ *     Hq % Hkv == 0, Hq/Hkv <= 16, kv_len[b] >= q_len[b] >= 1.
+ */
+#ifndef SPEC_VERIFY_H
+#define SPEC_VERIFY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SPEC_K_MAX 8
+#define SPEC_BLOCK_SIZE 16
+#define SPEC_NUM_COUNTERS 8
+
+typedef enum {
+    SPEC_OK = 0,
+    SPEC_EINVAL = -1,       /* malformed argument (null pointer, bad size, k_b > SPEC_K_MAX, ...) */
+    SPEC_EUNSUPPORTED = -2, /* well-formed but outside the supported shapes/dtypes/layouts */
+    SPEC_EWORKSPACE = -3,   /* workspace missing, misaligned or too small */
+    SPEC_EHIP = -4          /* a HIP call failed */
+} spec_status;
+
+typedef enum { SPEC_F32 = 0, SPEC_BF16 = 1 } spec_dtype;
+
+/*
+ * Page layouts of the KV cache (the paper leaves the layout to the serving
+ * engine's memory manager).  A page holds SPEC_BLOCK_SIZE consecutive tokens
+ * of one request for all KV heads; logical token t of request b is in page
+ * block_table[b][t / 16], slot t % 16.
+ *   SPEC_KV_TOKEN_MAJOR: K and V are [num_blocks][Hkv][16][d].
+ *   SPEC_KV_MFMA: bf16 only.  K is [num_blocks][Hkv][d/8][16][8] (eight
+ *     consecutive head dims of one token are 16 contiguous bytes, the 16
+ *     tokens of a page follow each other), V is [num_blocks][Hkv][d][16]
+ *     (the 16 tokens of one head dim are 32 contiguous bytes).  Both are the
+ *     operand order of the gfx950 matrix instructions, so a wavefront loads a
+ *     page with fully coalesced 16- and 8-byte-per-lane reads.
+ */
+typedef enum { SPEC_KV_TOKEN_MAJOR = 0, SPEC_KV_MFMA = 1 } spec_kv_layout;
+
+/* Lookahead attention of the k_b+1 query positions (Section 2.2, Section 4). */
+typedef struct {
+    int32_t B;                  /* requests */
+    int32_t Hq, Hkv;            /* query heads, KV heads (query head h reads KV head h / (Hq/Hkv)) */
+    int32_t d;                  /* head dim: 64 or 128 */
+    int32_t block_size;         /* must be SPEC_BLOCK_SIZE */
+    int32_t num_blocks;         /* pages in the pool */
+    int32_t max_blocks_per_req; /* row length of block_table */
+    int32_t T;                  /* sum_b q_len[b], q_len[b] = k_b + 1 */
+    int32_t qkv_dtype;          /* spec_dtype of q, k_cache, v_cache; out is fp32 */
+    int32_t kv_layout;          /* spec_kv_layout */
+    const void *q;              /* [T][Hq][d], rows packed by request: rows cu_q_len[b]..cu_q_len[b+1]-1 */
+    const void *k_cache;        /* page pool, see spec_kv_layout */
+    const void *v_cache;
+    const int32_t *block_table; /* [B][max_blocks_per_req]; entries past ceil(kv_len/16) are not read */
+    const int32_t *kv_len;      /* [B] valid KV tokens, INCLUDING this step's q_len[b] new tokens:
+                                   query j sits at position kv_len[b]-q_len[b]+j and sees keys 0..that */
+    const int32_t *cu_q_len;    /* [B+1] exclusive prefix sum of q_len */
+    float softmax_scale;        /* 0 means 1/sqrt(d) */
+    float *out;                 /* [T][Hq][d] fp32 */
+    const int32_t *host_kv_len;   /* HOST copy of kv_len, used to plan the split over the KV length */
+    const int32_t *host_cu_q_len; /* HOST copy of cu_q_len */
+} spec_attn_args;
+
+/*
+ * Rejection sampling with bonus token (Section 4's acceptance phase; the
+ * accept rule is the cited speculative-sampling method's: accept draft token
+ * x_i iff u_i < p_i(x_i)/q_i(x_i), p = softmax(target row), q = softmax(draft
+ * row); at the first rejection draw the next token from the normalised
+ * positive part of p - q, after k_b acceptances draw it from the last target
+ * row).
+ *
+ * Random numbers: Philox4x32-10, key = (seed low 32, seed high 32), counter =
+ * (index, b, step low 32, (step bits 32..55) << 8 | stream).  Stream 0, index
+ * i, word 0 gives the accept uniform u = (word >> 8) * 2^-24 in [0,1).  Stream
+ * 1, index v >> 2, word v & 3 gives U' = ((word >> 8) + 1) * 2^-24 in (0,1];
+ * the next token is argmax_v r_v / (-log U'_v) (an exponential race, i.e. a
+ * draw with probability proportional to the weights r_v; weights 0 never win,
+ * equal scores go to the lowest v).
+ */
+typedef struct {
+    int32_t B, V, T;
+    const float *target_logits;   /* [T][V]; request b owns rows cu_q_len[b] .. cu_q_len[b]+k_b */
+    const float *draft_logits;    /* [T-B][V]; request b owns rows cu_q_len[b]-b .. +k_b-1; row i produced x_i */
+    const int32_t *draft_tokens;  /* [T-B] */
+    const int32_t *cu_q_len;      /* [B+1] */
+    const int32_t *host_cu_q_len; /* HOST copy (validation and launch planning) */
+    uint64_t philox_seed;
+    uint64_t philox_step;
+    int32_t *accepted_len;        /* [B] out: m_b in [0, k_b] (draft tokens only, bonus not counted) */
+    int32_t *next_token;          /* [B] out: correction or bonus token */
+    int32_t *out_tokens;          /* optional [B][SPEC_K_MAX+1]: accepted tokens, next token, -1 padding */
+    int64_t *counters;            /* [SPEC_NUM_COUNTERS], ADDED to (caller zeroes):
+                                     [0] proposed  sum k_b
+                                     [1] accepted  sum m_b
+                                     [2] attempted sum min(m_b+1, k_b)  (accept tests evaluated)
+                                     [3] emitted   sum (m_b+1)          (goodput numerator, Eq. 1)
+                                     [4] near ties: evaluated accept tests with |u - p/q| < 1e-6
+                                     [5] requests
+                                     [6],[7] reserved, untouched */
+    double *debug_u_ratio;        /* optional [T-B][2]: u and p/q of each evaluated accept test, NaN otherwise */
+} spec_reject_args;
+
+/* Host-only: bytes of workspace the three calls below need for these shapes
+ * (either argument may be NULL).  Returns 0 if the arguments are malformed.
+ * The workspace must be 256-byte aligned device memory; its contents need no
+ * initialisation and are undefined afterwards. */
+size_t spec_verify_workspace_bytes(const spec_attn_args *attn, const spec_reject_args *reject);
+
+/* (a) only: writes attn->out. */
+spec_status spec_verify_attn(const spec_attn_args *attn, void *workspace, size_t workspace_bytes,
+                             void *hip_stream);
+
+/* (b) only: writes accepted_len, next_token, out_tokens, debug_u_ratio; adds to counters. */
+spec_status spec_reject_sample(const spec_reject_args *reject, void *workspace, size_t workspace_bytes,
+                               void *hip_stream);
+
+/* The whole step: (a) then (b) on one stream.  The logits do not depend on
+ * attn->out inside this library (the layers between them belong to the model). */
+spec_status spec_verify_step(const spec_attn_args *attn, const spec_reject_args *reject, void *workspace,
+                             size_t workspace_bytes, void *hip_stream);
+
+/* Host-only validation, exactly what the calls above run first. */
+spec_status spec_validate_attn(const spec_attn_args *attn);
+spec_status spec_validate_reject(const spec_reject_args *reject);
+
+/* Re-tile a token-major bf16 page pool [num_blocks][Hkv][16][d] into the
+ * SPEC_KV_MFMA layout (dst_k, dst_v; same byte sizes; must not alias the sources). */
+spec_status spec_kv_repack_mfma(const void *src_k, const void *src_v, void *dst_k, void *dst_v,
+                                int32_t num_blocks, int32_t Hkv, int32_t d, void *hip_stream);
+
+const char *spec_status_string(spec_status status);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int32_t spec_verify_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPEC_VERIFY_H */

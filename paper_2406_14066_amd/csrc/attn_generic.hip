@@ -1,0 +1,203 @@
+// Lookahead attention, generic kernels (Section 2.2 / Section 4 of arXiv
+// 2406.14066: the k+1 query positions of a request are scored against its
+// cached keys and values, query j seeing keys 0 .. kv_len - q_len + j).
+//
+//   attn_generic_kernel   any dtype (fp32, bf16) and page layout, scalar fp32
+//                         arithmetic: one block per (KV chunk, query head,
+//                         query row), one thread per key of the chunk.  This is
+//                         the fp32 path and the fallback for shapes the
+//                         matrix-instruction kernel does not take.
+//   attn_combine_kernel   merges the per-chunk partial results of either
+//                         attention kernel: out = sum_c w_c acc_c / sum_c w_c l_c,
+//                         w_c = 2^(m_c - max_c m_c).
+//   kv_repack_kernel      token-major pages -> matrix-instruction page layout.
+//
+// Scores are kept in base-2 units (the softmax scale is folded with log2 e).
+#include "common.h"
+
+#include <math.h>
+
+namespace specv {
+
+namespace {
+
+constexpr int kChunkThreads = 256;
+
+__device__ __forceinline__ float load_as_float(const float *p, size_t i) { return p[i]; }
+__device__ __forceinline__ float load_as_float(const uint16_t *p, size_t i)
+{
+    return __uint_as_float((uint32_t)p[i] << 16);
+}
+
+// index of K/V element (page, kv head, slot, dim) in the two page layouts
+__device__ __forceinline__ size_t k_index(int layout, int page, int Hkv, int kvh, int slot, int c, int d)
+{
+    const size_t head = (size_t)page * Hkv + kvh;
+    if (layout == SPEC_KV_TOKEN_MAJOR) return (head * SPEC_BLOCK_SIZE + slot) * d + c;
+    return ((head * (d >> 3) + (c >> 3)) * SPEC_BLOCK_SIZE + slot) * 8 + (c & 7);
+}
+
+__device__ __forceinline__ size_t v_index(int layout, int page, int Hkv, int kvh, int slot, int c, int d)
+{
+    const size_t head = (size_t)page * Hkv + kvh;
+    if (layout == SPEC_KV_TOKEN_MAJOR) return (head * SPEC_BLOCK_SIZE + slot) * d + c;
+    return (head * d + c) * SPEC_BLOCK_SIZE + slot;
+}
+
+// request that owns packed query row `row`: largest b with cu_q_len[b] <= row
+__device__ __forceinline__ int find_request(const int32_t *cu_q_len, int B, int row)
+{
+    int lo = 0, hi = B - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (cu_q_len[mid] <= row) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+template <typename KV_T>
+__global__ __launch_bounds__(kChunkThreads) void attn_generic_kernel(AttnParams p)
+{
+    const int tid = threadIdx.x;
+    const int chunk = blockIdx.x;
+    const int h = blockIdx.y;
+    const int row = blockIdx.z;
+    const int b = find_request(p.cu_q_len, p.B, row);
+    const int q_len = p.cu_q_len[b + 1] - p.cu_q_len[b];
+    const int j = row - p.cu_q_len[b];
+    const int L = p.kv_len[b];
+    const int nchunks = (L + p.chunk_tokens - 1) / p.chunk_tokens;
+    if (chunk >= nchunks) return;
+    const int last_visible = L - q_len + j;
+    const int kvh = h / (p.Hq / p.Hkv);
+    const int d = p.d;
+
+    __shared__ float sh_q[128];
+    __shared__ float sh_p[kChunkThreads];
+    __shared__ int sh_page[kChunkThreads];
+    __shared__ float sh_red[kChunkThreads / kWave];
+
+    const KV_T *q = static_cast<const KV_T *>(p.q);
+    const KV_T *kc = static_cast<const KV_T *>(p.k_cache);
+    const KV_T *vc = static_cast<const KV_T *>(p.v_cache);
+    if (tid < d) sh_q[tid] = load_as_float(q, ((size_t)row * p.Hq + h) * d + tid);
+    __syncthreads();
+
+    // one key per thread (chunk_tokens == blockDim.x)
+    const int token = chunk * p.chunk_tokens + tid;
+    const bool visible = tid < p.chunk_tokens && token <= last_visible;
+    float score = -INFINITY;
+    int page = 0;
+    if (visible) {
+        page = p.block_table[(size_t)b * p.max_blocks_per_req + token / SPEC_BLOCK_SIZE];
+        const int slot = token % SPEC_BLOCK_SIZE;
+        float dot = 0.0f;
+        for (int c = 0; c < d; ++c)
+            dot = fmaf(sh_q[c], load_as_float(kc, k_index(p.kv_layout, page, p.Hkv, kvh, slot, c, d)), dot);
+        score = dot * p.scale_log2;
+    }
+    sh_page[tid] = page;
+
+    // block maximum
+    float mx = score;
+    for (int off = kWave / 2; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+    if (tid % kWave == 0) sh_red[tid / kWave] = mx;
+    __syncthreads();
+    mx = kEmptyMax;
+    for (int w = 0; w < kChunkThreads / kWave; ++w) mx = fmaxf(mx, sh_red[w]);
+    __syncthreads();
+
+    const float prob = visible ? __builtin_amdgcn_exp2f(score - mx) : 0.0f;
+    sh_p[tid] = prob;
+    float sum = prob;
+    for (int off = kWave / 2; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
+    if (tid % kWave == 0) sh_red[tid / kWave] = sum;
+    __syncthreads();
+    sum = 0.0f;
+    for (int w = 0; w < kChunkThreads / kWave; ++w) sum += sh_red[w];
+
+    // weighted sum of values: one head dim per thread
+    const size_t slot_index = ((size_t)row * p.Hq + h) * p.max_chunks + chunk;
+    if (tid < d) {
+        const int ntok = min(p.chunk_tokens, last_visible - chunk * p.chunk_tokens + 1);
+        float acc = 0.0f;
+        for (int t = 0; t < ntok; ++t) {
+            const int slot = (chunk * p.chunk_tokens + t) % SPEC_BLOCK_SIZE;
+            acc = fmaf(sh_p[t], load_as_float(vc, v_index(p.kv_layout, sh_page[t], p.Hkv, kvh, slot, tid, d)), acc);
+        }
+        p.ws_acc[slot_index * d + tid] = acc;
+    }
+    if (tid == 0) {
+        p.ws_ml[slot_index * 2 + 0] = mx;
+        p.ws_ml[slot_index * 2 + 1] = sum;
+    }
+}
+
+// grid = T*Hq blocks of d threads
+__global__ void attn_combine_kernel(AttnParams p)
+{
+    const int row = blockIdx.x / p.Hq;
+    const int h = blockIdx.x % p.Hq;
+    const int tid = threadIdx.x;
+    const int b = find_request(p.cu_q_len, p.B, row);
+    const int nchunks = (p.kv_len[b] + p.chunk_tokens - 1) / p.chunk_tokens;
+    const size_t base = ((size_t)row * p.Hq + h) * p.max_chunks;
+    float mx = kEmptyMax;
+    for (int c = 0; c < nchunks; ++c) mx = fmaxf(mx, p.ws_ml[(base + c) * 2]);
+    float denom = 0.0f, acc = 0.0f;
+    for (int c = 0; c < nchunks; ++c) {
+        const float w = __builtin_amdgcn_exp2f(p.ws_ml[(base + c) * 2] - mx);
+        denom = fmaf(w, p.ws_ml[(base + c) * 2 + 1], denom);
+        acc = fmaf(w, p.ws_acc[(base + c) * p.d + tid], acc);
+    }
+    p.out[((size_t)row * p.Hq + h) * p.d + tid] = acc / denom;
+}
+
+// one thread per (page, kv head, slot, group of 8 dims)
+__global__ void kv_repack_kernel(const uint16_t *src_k, const uint16_t *src_v, uint16_t *dst_k, uint16_t *dst_v,
+                                 size_t heads, int d)
+{
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int groups = d >> 3;
+    const size_t total = heads * SPEC_BLOCK_SIZE * groups;
+    if (idx >= total) return;
+    const int g = (int)(idx % groups);
+    const int slot = (int)((idx / groups) % SPEC_BLOCK_SIZE);
+    const size_t head = idx / ((size_t)groups * SPEC_BLOCK_SIZE);
+    const size_t src = (head * SPEC_BLOCK_SIZE + slot) * d + (size_t)g * 8;
+    const uint4 kk = *reinterpret_cast<const uint4 *>(src_k + src);
+    *reinterpret_cast<uint4 *>(dst_k + ((head * groups + g) * SPEC_BLOCK_SIZE + slot) * 8) = kk;
+    for (int e = 0; e < 8; ++e) dst_v[(head * d + g * 8 + e) * SPEC_BLOCK_SIZE + slot] = src_v[src + e];
+}
+
+}  // namespace
+
+hipError_t launch_attn_generic(const AttnParams &p, int dtype, hipStream_t stream)
+{
+    dim3 grid(p.max_chunks, p.Hq, p.T);
+    if (dtype == SPEC_F32)
+        hipLaunchKernelGGL(attn_generic_kernel<float>, grid, dim3(kChunkThreads), 0, stream, p);
+    else
+        hipLaunchKernelGGL(attn_generic_kernel<uint16_t>, grid, dim3(kChunkThreads), 0, stream, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_attn_combine(const AttnParams &p, hipStream_t stream)
+{
+    hipLaunchKernelGGL(attn_combine_kernel, dim3(p.T * p.Hq), dim3(p.d), 0, stream, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_kv_repack(const void *src_k, const void *src_v, void *dst_k, void *dst_v, int32_t num_blocks,
+                            int32_t Hkv, int32_t d, hipStream_t stream)
+{
+    const size_t heads = (size_t)num_blocks * Hkv;
+    const size_t total = heads * SPEC_BLOCK_SIZE * (d >> 3);
+    const unsigned blocks = (unsigned)((total + 255) / 256);
+    hipLaunchKernelGGL(kv_repack_kernel, dim3(blocks), dim3(256), 0, stream, static_cast<const uint16_t *>(src_k),
+                       static_cast<const uint16_t *>(src_v), static_cast<uint16_t *>(dst_k),
+                       static_cast<uint16_t *>(dst_v), heads, d);
+    return hipGetLastError();
+}
+
+}  // namespace specv

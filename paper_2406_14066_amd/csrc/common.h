@@ -1,0 +1,86 @@
+// Shared declarations of the HIP library's translation units (host planning
+// structs and kernel launchers).  Nothing here is used by the CPU oracle.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "spec_verify.h"
+
+namespace specv {
+
+constexpr int kWave = 64;
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr double kLog2eD = 1.4426950408889634074;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kEmptyMax = -1.0e30f;  // running maximum of a row that has seen no key yet
+
+// ---------------------------------------------------------------- attention
+// Split of the KV length: every request is cut into chunks of `chunk_tokens`
+// tokens; chunk c of a request covers tokens [c*chunk, min((c+1)*chunk, kv_len)).
+// Each (query row, query head, chunk) owns one partial result in the workspace:
+//   acc  [T*Hq][max_chunks][d]  un-normalised sum_t exp(s_t - m) V_t
+//   ml   [T*Hq][max_chunks][2]  running maximum m and sum l of exp(s_t - m)
+struct AttnPlan {
+    int32_t chunk_tokens;
+    int32_t max_chunks;
+    int32_t max_q_len;
+    int32_t use_mfma;      // 1: bf16 matrix-instruction kernel, 0: generic kernel
+    int32_t row_tiles;     // 16-row tiles covering max_q_len * (Hq/Hkv) rows (mfma kernel)
+    size_t acc_bytes;
+    size_t ml_bytes;
+    size_t total_bytes;
+};
+
+struct AttnParams {
+    int32_t B, Hq, Hkv, d, num_blocks, max_blocks_per_req, T;
+    int32_t kv_layout;
+    int32_t chunk_tokens, max_chunks;
+    float scale_log2;  // softmax scale times log2(e): scores are kept in base-2 units
+    const void *q, *k_cache, *v_cache;
+    const int32_t *block_table, *kv_len, *cu_q_len;
+    float *out;
+    float *ws_acc;
+    float *ws_ml;
+};
+
+hipError_t launch_attn_generic(const AttnParams &p, int dtype, hipStream_t stream);
+hipError_t launch_attn_mfma(const AttnParams &p, int row_tiles, hipStream_t stream);
+hipError_t launch_attn_combine(const AttnParams &p, hipStream_t stream);
+hipError_t launch_kv_repack(const void *src_k, const void *src_v, void *dst_k, void *dst_v, int32_t num_blocks,
+                            int32_t Hkv, int32_t d, hipStream_t stream);
+
+// ---------------------------------------------------------------- rejection
+struct RowStat {   // one vocabulary segment of one logit row
+    double sum;    // sum_v 2^(x_v * log2(e) - off2)
+    float off2;    // integer-valued base-2 offset, about max_v x_v * log2(e)
+    float pad;
+};
+
+struct RejectPlan {
+    int32_t stat_segments, stat_seg_len;   // segments per row in the statistics pass
+    int32_t race_segments, race_seg_len;   // blocks per request in the race pass
+    size_t stats_off, stats_bytes;
+    size_t race_off, race_bytes;
+    size_t ticket_off, ticket_bytes;
+    size_t total_bytes;
+};
+
+struct RejectParams {
+    int32_t B, V, T;
+    const float *target_logits, *draft_logits;
+    const int32_t *draft_tokens, *cu_q_len;
+    uint32_t seed_lo, seed_hi, step_lo, step_hi24;
+    int32_t *accepted_len, *next_token, *out_tokens;
+    unsigned long long *counters;
+    double *debug_u_ratio;
+    int32_t stat_segments, stat_seg_len, race_segments, race_seg_len;
+    RowStat *stats;
+    unsigned long long *race_partial;
+    int32_t *tickets;
+};
+
+hipError_t launch_logit_stats(const RejectParams &p, hipStream_t stream);
+hipError_t launch_accept_race(const RejectParams &p, hipStream_t stream);
+
+}  // namespace specv

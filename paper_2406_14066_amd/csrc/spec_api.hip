@@ -1,0 +1,286 @@
+// C ABI of the speculative-verification library: host-side validation, launch
+// planning and the exported entry points declared in spec_verify.h.
+#include "common.h"
+
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+namespace specv {
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+spec_status validate_attn(const spec_attn_args *a)
+{
+    if (a == nullptr) return SPEC_EINVAL;
+    if (a->B < 1 || a->Hq < 1 || a->Hkv < 1 || a->num_blocks < 1 || a->max_blocks_per_req < 1 || a->T < a->B)
+        return SPEC_EINVAL;
+    if (a->q == nullptr || a->k_cache == nullptr || a->v_cache == nullptr || a->block_table == nullptr ||
+        a->kv_len == nullptr || a->cu_q_len == nullptr || a->out == nullptr || a->host_kv_len == nullptr ||
+        a->host_cu_q_len == nullptr)
+        return SPEC_EINVAL;
+    if (a->Hq % a->Hkv != 0) return SPEC_EINVAL;
+    if (!(a->softmax_scale >= 0.0f) || isinf(a->softmax_scale)) return SPEC_EINVAL;
+    if (a->qkv_dtype != SPEC_F32 && a->qkv_dtype != SPEC_BF16) return SPEC_EINVAL;
+    if (a->kv_layout != SPEC_KV_TOKEN_MAJOR && a->kv_layout != SPEC_KV_MFMA) return SPEC_EINVAL;
+    if (a->host_cu_q_len[0] != 0 || a->host_cu_q_len[a->B] != a->T) return SPEC_EINVAL;
+    for (int b = 0; b < a->B; ++b) {
+        const int q_len = a->host_cu_q_len[b + 1] - a->host_cu_q_len[b];
+        const int len = a->host_kv_len[b];
+        if (q_len < 1 || q_len > SPEC_K_MAX + 1) return SPEC_EINVAL;
+        if (len < q_len) return SPEC_EINVAL;
+        if ((len + SPEC_BLOCK_SIZE - 1) / SPEC_BLOCK_SIZE > a->max_blocks_per_req) return SPEC_EINVAL;
+    }
+    if (a->block_size != SPEC_BLOCK_SIZE) return SPEC_EUNSUPPORTED;
+    if (a->d != 64 && a->d != 128) return SPEC_EUNSUPPORTED;
+    if (a->Hq / a->Hkv > 16) return SPEC_EUNSUPPORTED;
+    if (a->kv_layout == SPEC_KV_MFMA && a->qkv_dtype != SPEC_BF16) return SPEC_EUNSUPPORTED;
+    if (a->T > 65535 || a->Hq > 65535) return SPEC_EUNSUPPORTED;
+    return SPEC_OK;
+}
+
+spec_status validate_reject(const spec_reject_args *r)
+{
+    if (r == nullptr) return SPEC_EINVAL;
+    if (r->B < 1 || r->V < 1 || r->T < r->B) return SPEC_EINVAL;
+    if (r->target_logits == nullptr || r->cu_q_len == nullptr || r->host_cu_q_len == nullptr ||
+        r->accepted_len == nullptr || r->next_token == nullptr || r->counters == nullptr)
+        return SPEC_EINVAL;
+    if (r->T > r->B && (r->draft_logits == nullptr || r->draft_tokens == nullptr)) return SPEC_EINVAL;
+    if (r->host_cu_q_len[0] != 0 || r->host_cu_q_len[r->B] != r->T) return SPEC_EINVAL;
+    for (int b = 0; b < r->B; ++b) {
+        const int q_len = r->host_cu_q_len[b + 1] - r->host_cu_q_len[b];
+        if (q_len < 1 || q_len > SPEC_K_MAX + 1) return SPEC_EINVAL;
+    }
+    if (r->V % 4 != 0) return SPEC_EUNSUPPORTED;  // rows are read as 16-byte vectors
+    if (r->B > 65535 || 2 * (int64_t)r->T - r->B > 65535) return SPEC_EUNSUPPORTED;
+    if ((reinterpret_cast<uintptr_t>(r->target_logits) & 15) != 0 ||
+        (reinterpret_cast<uintptr_t>(r->draft_logits) & 15) != 0)
+        return SPEC_EINVAL;
+    return SPEC_OK;
+}
+
+// Split of the KV length.  The matrix-instruction kernel runs one block per
+// (request, KV head, chunk); the chunk is sized so that the launch has about
+// eight blocks per compute unit, in multiples of the 64 tokens a block's four
+// wavefronts take per round.
+AttnPlan plan_attn(const spec_attn_args *a)
+{
+    AttnPlan pl;
+    memset(&pl, 0, sizeof pl);
+    int64_t total = 0;
+    int max_len = 0, max_q = 0;
+    for (int b = 0; b < a->B; ++b) {
+        total += a->host_kv_len[b];
+        if (a->host_kv_len[b] > max_len) max_len = a->host_kv_len[b];
+        const int q_len = a->host_cu_q_len[b + 1] - a->host_cu_q_len[b];
+        if (q_len > max_q) max_q = q_len;
+    }
+    pl.max_q_len = max_q;
+    const int group = a->Hq / a->Hkv;
+    const int rows = max_q * group;
+    pl.row_tiles = (rows + 15) / 16;
+    pl.use_mfma = (a->qkv_dtype == SPEC_BF16 && a->kv_layout == SPEC_KV_MFMA && a->d == 128 && pl.row_tiles <= 3) ? 1 : 0;
+    // diagnostic switch: SPEC_VERIFY_FORCE_GENERIC=1 routes every shape through the generic kernel
+    const char *force = getenv("SPEC_VERIFY_FORCE_GENERIC");
+    if (force != nullptr && force[0] == '1') pl.use_mfma = 0;
+    if (pl.use_mfma) {
+        const int64_t target_blocks = 2048;
+        int64_t chunk = (total * a->Hkv + target_blocks - 1) / target_blocks;
+        chunk = (chunk + 63) / 64 * 64;
+        if (chunk < 64) chunk = 64;
+        if (chunk > 4096) chunk = 4096;
+        pl.chunk_tokens = (int32_t)chunk;
+    } else {
+        pl.chunk_tokens = 256;  // one key per thread of the generic kernel
+    }
+    pl.max_chunks = (max_len + pl.chunk_tokens - 1) / pl.chunk_tokens;
+    const size_t slots = (size_t)a->T * a->Hq * pl.max_chunks;
+    pl.acc_bytes = align_up(slots * a->d * sizeof(float));
+    pl.ml_bytes = align_up(slots * 2 * sizeof(float));
+    pl.total_bytes = pl.acc_bytes + pl.ml_bytes;
+    return pl;
+}
+
+RejectPlan plan_reject(const spec_reject_args *r, size_t base)
+{
+    RejectPlan pl;
+    memset(&pl, 0, sizeof pl);
+    const int rows = 2 * r->T - r->B;
+    // statistics pass: aim for >= 2048 blocks, segments of >= 1024 logits
+    int segs = (2048 + rows - 1) / rows;
+    const int max_by_len = (r->V + 1023) / 1024;
+    if (segs > max_by_len) segs = max_by_len;
+    if (segs > 32) segs = 32;
+    if (segs < 1) segs = 1;
+    int seg_len = (r->V + segs - 1) / segs;
+    seg_len = (seg_len + 3) / 4 * 4;
+    pl.stat_seg_len = seg_len;
+    pl.stat_segments = (r->V + seg_len - 1) / seg_len;
+    // race pass: aim for >= 1024 blocks, segments of >= 1024 vocabulary ids
+    int rsegs = (1024 + r->B - 1) / r->B;
+    if (rsegs > max_by_len) rsegs = max_by_len;
+    if (rsegs > 64) rsegs = 64;
+    if (rsegs < 1) rsegs = 1;
+    int rlen = (r->V + rsegs - 1) / rsegs;
+    rlen = (rlen + 3) / 4 * 4;
+    pl.race_seg_len = rlen;
+    pl.race_segments = (r->V + rlen - 1) / rlen;
+
+    pl.stats_off = base;
+    pl.stats_bytes = align_up((size_t)rows * pl.stat_segments * sizeof(RowStat));
+    pl.race_off = pl.stats_off + pl.stats_bytes;
+    pl.race_bytes = align_up((size_t)r->B * pl.race_segments * sizeof(unsigned long long));
+    pl.ticket_off = pl.race_off + pl.race_bytes;
+    pl.ticket_bytes = align_up((size_t)r->B * sizeof(int32_t));
+    pl.total_bytes = pl.stats_bytes + pl.race_bytes + pl.ticket_bytes;
+    return pl;
+}
+
+spec_status check_workspace(void *ws, size_t have, size_t need)
+{
+    if (ws == nullptr || (reinterpret_cast<uintptr_t>(ws) & (kAlign - 1)) != 0 || have < need) return SPEC_EWORKSPACE;
+    return SPEC_OK;
+}
+
+spec_status run_attn(const spec_attn_args *a, const AttnPlan &pl, char *ws, hipStream_t stream)
+{
+    AttnParams p;
+    memset(&p, 0, sizeof p);
+    p.B = a->B; p.Hq = a->Hq; p.Hkv = a->Hkv; p.d = a->d;
+    p.num_blocks = a->num_blocks; p.max_blocks_per_req = a->max_blocks_per_req; p.T = a->T;
+    p.kv_layout = a->kv_layout;
+    p.chunk_tokens = pl.chunk_tokens; p.max_chunks = pl.max_chunks;
+    const double scale = a->softmax_scale > 0.0f ? (double)a->softmax_scale : 1.0 / sqrt((double)a->d);
+    p.scale_log2 = (float)(scale * kLog2eD);
+    p.q = a->q; p.k_cache = a->k_cache; p.v_cache = a->v_cache;
+    p.block_table = a->block_table; p.kv_len = a->kv_len; p.cu_q_len = a->cu_q_len;
+    p.out = a->out;
+    p.ws_acc = reinterpret_cast<float *>(ws);
+    p.ws_ml = reinterpret_cast<float *>(ws + pl.acc_bytes);
+    hipError_t err = pl.use_mfma ? launch_attn_mfma(p, pl.row_tiles, stream) : launch_attn_generic(p, a->qkv_dtype, stream);
+    if (err != hipSuccess) return SPEC_EHIP;
+    err = launch_attn_combine(p, stream);
+    return err == hipSuccess ? SPEC_OK : SPEC_EHIP;
+}
+
+spec_status run_reject(const spec_reject_args *r, const RejectPlan &pl, char *ws, hipStream_t stream)
+{
+    RejectParams p;
+    memset(&p, 0, sizeof p);
+    p.B = r->B; p.V = r->V; p.T = r->T;
+    p.target_logits = r->target_logits; p.draft_logits = r->draft_logits;
+    p.draft_tokens = r->draft_tokens; p.cu_q_len = r->cu_q_len;
+    p.seed_lo = (uint32_t)(r->philox_seed & 0xFFFFFFFFull);
+    p.seed_hi = (uint32_t)(r->philox_seed >> 32);
+    p.step_lo = (uint32_t)(r->philox_step & 0xFFFFFFFFull);
+    p.step_hi24 = (uint32_t)((r->philox_step >> 32) & 0xFFFFFFull);
+    p.accepted_len = r->accepted_len; p.next_token = r->next_token; p.out_tokens = r->out_tokens;
+    p.counters = reinterpret_cast<unsigned long long *>(r->counters);
+    p.debug_u_ratio = r->debug_u_ratio;
+    p.stat_segments = pl.stat_segments; p.stat_seg_len = pl.stat_seg_len;
+    p.race_segments = pl.race_segments; p.race_seg_len = pl.race_seg_len;
+    p.stats = reinterpret_cast<RowStat *>(ws + pl.stats_off);
+    p.race_partial = reinterpret_cast<unsigned long long *>(ws + pl.race_off);
+    p.tickets = reinterpret_cast<int32_t *>(ws + pl.ticket_off);
+    hipError_t err = launch_logit_stats(p, stream);
+    if (err != hipSuccess) return SPEC_EHIP;
+    err = launch_accept_race(p, stream);
+    return err == hipSuccess ? SPEC_OK : SPEC_EHIP;
+}
+
+}  // namespace
+
+}  // namespace specv
+
+using namespace specv;
+
+extern "C" {
+
+spec_status spec_validate_attn(const spec_attn_args *attn) { return validate_attn(attn); }
+
+spec_status spec_validate_reject(const spec_reject_args *reject) { return validate_reject(reject); }
+
+size_t spec_verify_workspace_bytes(const spec_attn_args *attn, const spec_reject_args *reject)
+{
+    size_t total = 0;
+    if (attn != nullptr) {
+        if (validate_attn(attn) != SPEC_OK) return 0;
+        total += plan_attn(attn).total_bytes;
+    }
+    if (reject != nullptr) {
+        if (validate_reject(reject) != SPEC_OK) return 0;
+        total += plan_reject(reject, total).total_bytes;
+    }
+    return total;
+}
+
+spec_status spec_verify_attn(const spec_attn_args *attn, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    spec_status st = validate_attn(attn);
+    if (st != SPEC_OK) return st;
+    const AttnPlan pl = plan_attn(attn);
+    st = check_workspace(workspace, workspace_bytes, pl.total_bytes);
+    if (st != SPEC_OK) return st;
+    return run_attn(attn, pl, static_cast<char *>(workspace), static_cast<hipStream_t>(hip_stream));
+}
+
+spec_status spec_reject_sample(const spec_reject_args *reject, void *workspace, size_t workspace_bytes,
+                               void *hip_stream)
+{
+    spec_status st = validate_reject(reject);
+    if (st != SPEC_OK) return st;
+    const RejectPlan pl = plan_reject(reject, 0);
+    st = check_workspace(workspace, workspace_bytes, pl.total_bytes);
+    if (st != SPEC_OK) return st;
+    return run_reject(reject, pl, static_cast<char *>(workspace), static_cast<hipStream_t>(hip_stream));
+}
+
+spec_status spec_verify_step(const spec_attn_args *attn, const spec_reject_args *reject, void *workspace,
+                             size_t workspace_bytes, void *hip_stream)
+{
+    spec_status st = validate_attn(attn);
+    if (st != SPEC_OK) return st;
+    st = validate_reject(reject);
+    if (st != SPEC_OK) return st;
+    if (attn->B != reject->B || attn->T != reject->T) return SPEC_EINVAL;
+    const AttnPlan apl = plan_attn(attn);
+    const RejectPlan rpl = plan_reject(reject, apl.total_bytes);
+    st = check_workspace(workspace, workspace_bytes, apl.total_bytes + rpl.total_bytes);
+    if (st != SPEC_OK) return st;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    st = run_attn(attn, apl, static_cast<char *>(workspace), stream);
+    if (st != SPEC_OK) return st;
+    return run_reject(reject, rpl, static_cast<char *>(workspace), stream);
+}
+
+spec_status spec_kv_repack_mfma(const void *src_k, const void *src_v, void *dst_k, void *dst_v, int32_t num_blocks,
+                                int32_t Hkv, int32_t d, void *hip_stream)
+{
+    if (src_k == nullptr || src_v == nullptr || dst_k == nullptr || dst_v == nullptr || num_blocks < 1 || Hkv < 1)
+        return SPEC_EINVAL;
+    if (src_k == dst_k || src_v == dst_v || src_k == dst_v || src_v == dst_k) return SPEC_EINVAL;
+    if (d != 64 && d != 128) return SPEC_EUNSUPPORTED;
+    const hipError_t err = launch_kv_repack(src_k, src_v, dst_k, dst_v, num_blocks, Hkv, d,
+                                            static_cast<hipStream_t>(hip_stream));
+    return err == hipSuccess ? SPEC_OK : SPEC_EHIP;
+}
+
+const char *spec_status_string(spec_status status)
+{
+    switch (status) {
+        case SPEC_OK: return "ok";
+        case SPEC_EINVAL: return "invalid argument";
+        case SPEC_EUNSUPPORTED: return "unsupported shape, dtype or layout";
+        case SPEC_EWORKSPACE: return "workspace missing, misaligned or too small";
+        case SPEC_EHIP: return "HIP call failed";
+    }
+    return "unknown status";
+}
+
+int32_t spec_verify_version(void) { return 100; }
+
+}  // extern "C"

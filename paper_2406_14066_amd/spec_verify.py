@@ -1,0 +1,225 @@
+"""Thin ctypes binding of ``libspec_verify.so`` (the C ABI in ``include/spec_verify.h``).
+
+Argument marshalling only: tensors are passed as raw device pointers, the
+stream as the raw ``hipStream_t`` of torch's current stream; every step of the
+path runs in the library's kernels.  There is no CPU fallback: if the library
+has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libspec_verify.so")
+
+K_MAX = 8
+BLOCK_SIZE = 16
+NUM_COUNTERS = 8
+
+SPEC_OK, SPEC_EINVAL, SPEC_EUNSUPPORTED, SPEC_EWORKSPACE, SPEC_EHIP = 0, -1, -2, -3, -4
+SPEC_F32, SPEC_BF16 = 0, 1
+KV_TOKEN_MAJOR, KV_MFMA = 0, 1
+
+COUNTER_NAMES = ("proposed", "accepted", "attempted", "emitted", "near_tie", "requests", "reserved6", "reserved7")
+
+
+class AttnArgs(C.Structure):
+    _fields_ = [
+        ("B", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32), ("d", C.c_int32),
+        ("block_size", C.c_int32), ("num_blocks", C.c_int32), ("max_blocks_per_req", C.c_int32),
+        ("T", C.c_int32), ("qkv_dtype", C.c_int32), ("kv_layout", C.c_int32),
+        ("q", C.c_void_p), ("k_cache", C.c_void_p), ("v_cache", C.c_void_p),
+        ("block_table", C.c_void_p), ("kv_len", C.c_void_p), ("cu_q_len", C.c_void_p),
+        ("softmax_scale", C.c_float),
+        ("out", C.c_void_p),
+        ("host_kv_len", C.c_void_p), ("host_cu_q_len", C.c_void_p),
+    ]
+
+
+class RejectArgs(C.Structure):
+    _fields_ = [
+        ("B", C.c_int32), ("V", C.c_int32), ("T", C.c_int32),
+        ("target_logits", C.c_void_p), ("draft_logits", C.c_void_p),
+        ("draft_tokens", C.c_void_p), ("cu_q_len", C.c_void_p), ("host_cu_q_len", C.c_void_p),
+        ("philox_seed", C.c_uint64), ("philox_step", C.c_uint64),
+        ("accepted_len", C.c_void_p), ("next_token", C.c_void_p), ("out_tokens", C.c_void_p),
+        ("counters", C.c_void_p), ("debug_u_ratio", C.c_void_p),
+    ]
+
+
+EXPORTS = (
+    "spec_verify_workspace_bytes", "spec_verify_attn", "spec_reject_sample", "spec_verify_step",
+    "spec_validate_attn", "spec_validate_reject", "spec_kv_repack_mfma", "spec_status_string",
+    "spec_verify_version",
+)
+
+_lib = None
+
+
+class SpecVerifyError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: %s (%d)" % (where, status_string(status), status))
+
+
+def lib():
+    """Loads the HIP library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                "libspec_verify.so is missing: build it first (python -c 'import __graft_entry__ as g; g.build()'). "
+                "There is no fallback path.")
+        L = C.CDLL(LIB_PATH)
+        L.spec_verify_workspace_bytes.argtypes = [C.POINTER(AttnArgs), C.POINTER(RejectArgs)]
+        L.spec_verify_workspace_bytes.restype = C.c_size_t
+        L.spec_verify_attn.argtypes = [C.POINTER(AttnArgs), C.c_void_p, C.c_size_t, C.c_void_p]
+        L.spec_verify_attn.restype = C.c_int
+        L.spec_reject_sample.argtypes = [C.POINTER(RejectArgs), C.c_void_p, C.c_size_t, C.c_void_p]
+        L.spec_reject_sample.restype = C.c_int
+        L.spec_verify_step.argtypes = [C.POINTER(AttnArgs), C.POINTER(RejectArgs), C.c_void_p, C.c_size_t, C.c_void_p]
+        L.spec_verify_step.restype = C.c_int
+        L.spec_validate_attn.argtypes = [C.POINTER(AttnArgs)]
+        L.spec_validate_attn.restype = C.c_int
+        L.spec_validate_reject.argtypes = [C.POINTER(RejectArgs)]
+        L.spec_validate_reject.restype = C.c_int
+        L.spec_kv_repack_mfma.argtypes = [C.c_void_p] * 4 + [C.c_int32] * 3 + [C.c_void_p]
+        L.spec_kv_repack_mfma.restype = C.c_int
+        L.spec_status_string.argtypes = [C.c_int]
+        L.spec_status_string.restype = C.c_char_p
+        L.spec_verify_version.argtypes = []
+        L.spec_verify_version.restype = C.c_int32
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().spec_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str):
+    if status != SPEC_OK:
+        raise SpecVerifyError(status, where)
+
+
+def _dev_ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _host_i32(a) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a), dtype=np.int32)
+
+
+def _stream_handle(stream) -> Optional[int]:
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream or None
+
+
+def make_attn_args(q, k_cache, v_cache, block_table, kv_len, cu_q_len, out, host_kv_len, host_cu_q_len,
+                   *, Hkv: int, kv_layout: int = KV_TOKEN_MAJOR, softmax_scale: float = 0.0,
+                   block_size: int = BLOCK_SIZE):
+    """Builds the argument struct from device tensors (torch) and host arrays (numpy).
+    Returns (struct, keepalive) -- keep `keepalive` referenced while the struct is in use."""
+    import torch
+    T, Hq, d = q.shape
+    if q.dtype == torch.float32:
+        dtype = SPEC_F32
+    elif q.dtype == torch.bfloat16:
+        dtype = SPEC_BF16
+    else:
+        raise TypeError("q must be float32 or bfloat16")
+    hk = _host_i32(host_kv_len)
+    hc = _host_i32(host_cu_q_len)
+    a = AttnArgs()
+    a.B = hk.shape[0]
+    a.Hq, a.Hkv, a.d = Hq, Hkv, d
+    a.block_size = block_size
+    a.num_blocks = k_cache.shape[0]
+    a.max_blocks_per_req = block_table.shape[1]
+    a.T = T
+    a.qkv_dtype = dtype
+    a.kv_layout = kv_layout
+    a.q, a.k_cache, a.v_cache = q.data_ptr(), k_cache.data_ptr(), v_cache.data_ptr()
+    a.block_table, a.kv_len, a.cu_q_len = block_table.data_ptr(), kv_len.data_ptr(), cu_q_len.data_ptr()
+    a.softmax_scale = softmax_scale
+    a.out = out.data_ptr()
+    a.host_kv_len = hk.ctypes.data
+    a.host_cu_q_len = hc.ctypes.data
+    return a, (hk, hc, q, k_cache, v_cache, block_table, kv_len, cu_q_len, out)
+
+
+def make_reject_args(target_logits, draft_logits, draft_tokens, cu_q_len, host_cu_q_len, accepted_len, next_token,
+                     counters, *, philox_seed: int, philox_step: int, out_tokens=None, debug_u_ratio=None):
+    hc = _host_i32(host_cu_q_len)
+    r = RejectArgs()
+    r.B = hc.shape[0] - 1
+    r.T, r.V = target_logits.shape
+    r.target_logits = target_logits.data_ptr()
+    r.draft_logits = _dev_ptr(draft_logits) if r.T > r.B else None
+    r.draft_tokens = _dev_ptr(draft_tokens) if r.T > r.B else None
+    r.cu_q_len = cu_q_len.data_ptr()
+    r.host_cu_q_len = hc.ctypes.data
+    r.philox_seed = philox_seed
+    r.philox_step = philox_step
+    r.accepted_len = accepted_len.data_ptr()
+    r.next_token = next_token.data_ptr()
+    r.out_tokens = _dev_ptr(out_tokens)
+    r.counters = counters.data_ptr()
+    r.debug_u_ratio = _dev_ptr(debug_u_ratio)
+    return r, (hc, target_logits, draft_logits, draft_tokens, cu_q_len, accepted_len, next_token, counters,
+               out_tokens, debug_u_ratio)
+
+
+def spec_verify_workspace_bytes(attn: Optional[AttnArgs], reject: Optional[RejectArgs]) -> int:
+    n = lib().spec_verify_workspace_bytes(C.byref(attn) if attn is not None else None,
+                                          C.byref(reject) if reject is not None else None)
+    if n == 0:
+        raise SpecVerifyError(SPEC_EINVAL, "spec_verify_workspace_bytes")
+    return int(n)
+
+
+def spec_validate_attn(attn: AttnArgs) -> int:
+    return int(lib().spec_validate_attn(C.byref(attn)))
+
+
+def spec_validate_reject(reject: RejectArgs) -> int:
+    return int(lib().spec_validate_reject(C.byref(reject)))
+
+
+def spec_verify_attn(attn: AttnArgs, workspace, stream=None) -> None:
+    _check(lib().spec_verify_attn(C.byref(attn), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                  _stream_handle(stream)), "spec_verify_attn")
+
+
+def spec_reject_sample(reject: RejectArgs, workspace, stream=None) -> None:
+    _check(lib().spec_reject_sample(C.byref(reject), workspace.data_ptr(),
+                                    workspace.numel() * workspace.element_size(), _stream_handle(stream)),
+           "spec_reject_sample")
+
+
+def spec_verify_step(attn: AttnArgs, reject: RejectArgs, workspace, stream=None) -> None:
+    _check(lib().spec_verify_step(C.byref(attn), C.byref(reject), workspace.data_ptr(),
+                                  workspace.numel() * workspace.element_size(), _stream_handle(stream)),
+           "spec_verify_step")
+
+
+def spec_kv_repack_mfma(src_k, src_v, dst_k, dst_v, stream=None) -> None:
+    nb, Hkv, bs, d = src_k.shape
+    assert bs == BLOCK_SIZE and src_k.element_size() == 2
+    _check(lib().spec_kv_repack_mfma(src_k.data_ptr(), src_v.data_ptr(), dst_k.data_ptr(), dst_v.data_ptr(),
+                                     nb, Hkv, d, _stream_handle(stream)), "spec_kv_repack_mfma")
+
+
+def spec_verify_version() -> int:
+    return int(lib().spec_verify_version())
+
+
+def alloc_workspace(nbytes: int, device="cuda"):
+    """A 256-byte aligned device buffer (torch's allocator aligns to 512)."""
+    import torch
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)

@@ -1,0 +1,157 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+symbol the header declares, and validates arguments before launching anything."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2406_14066_amd import spec_verify as sv
+
+ROOT = os.path.abspath(os.path.join(os.path.dirname(__file__), ".."))
+HEADER = os.path.join(ROOT, "include", "spec_verify.h")
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(spec_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_functions()
+    assert set(names) == set(sv.EXPORTS)
+    lib = C.CDLL(sv.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_version_and_status_strings():
+    assert sv.spec_verify_version() >= 100
+    seen = {sv.status_string(s) for s in (0, -1, -2, -3, -4)}
+    assert len(seen) == 5 and "ok" in seen
+    assert "unknown" in sv.status_string(-99)
+
+
+FAKE = 0x1000  # non-null, 16-byte aligned, never dereferenced: validation is host-only
+
+
+def _attn(B=2, Hq=4, Hkv=2, d=128, kv_len=(40, 20), q_len=(3, 2), max_blocks=4, dtype=sv.SPEC_BF16,
+          layout=sv.KV_MFMA):
+    hk = np.asarray(kv_len, dtype=np.int32)
+    hc = np.concatenate([[0], np.cumsum(q_len)]).astype(np.int32)
+    a = sv.AttnArgs()
+    a.B, a.Hq, a.Hkv, a.d = B, Hq, Hkv, d
+    a.block_size, a.num_blocks, a.max_blocks_per_req = 16, 16, max_blocks
+    a.T = int(hc[-1])
+    a.qkv_dtype, a.kv_layout = dtype, layout
+    for f in ("q", "k_cache", "v_cache", "block_table", "kv_len", "cu_q_len", "out"):
+        setattr(a, f, FAKE)
+    a.host_kv_len = hk.ctypes.data
+    a.host_cu_q_len = hc.ctypes.data
+    a._keep = (hk, hc)
+    return a
+
+
+def _reject(B=2, V=32, q_len=(3, 2)):
+    hc = np.concatenate([[0], np.cumsum(q_len)]).astype(np.int32)
+    r = sv.RejectArgs()
+    r.B, r.V, r.T = B, V, int(hc[-1])
+    for f in ("target_logits", "draft_logits", "draft_tokens", "cu_q_len", "accepted_len", "next_token", "counters"):
+        setattr(r, f, FAKE)
+    r.host_cu_q_len = hc.ctypes.data
+    r._keep = (hc,)
+    return r
+
+
+def test_validate_attn_accepts_good_arguments():
+    assert sv.spec_validate_attn(_attn()) == sv.SPEC_OK
+    assert sv.spec_validate_attn(_attn(dtype=sv.SPEC_F32, layout=sv.KV_TOKEN_MAJOR, d=64)) == sv.SPEC_OK
+
+
+@pytest.mark.parametrize("mutate,status", [
+    (lambda a: setattr(a, "q", None), sv.SPEC_EINVAL),
+    (lambda a: setattr(a, "out", None), sv.SPEC_EINVAL),
+    (lambda a: setattr(a, "host_kv_len", None), sv.SPEC_EINVAL),
+    (lambda a: setattr(a, "Hkv", 3), sv.SPEC_EINVAL),             # Hq % Hkv != 0
+    (lambda a: setattr(a, "T", 6), sv.SPEC_EINVAL),               # != cu_q_len[B]
+    (lambda a: setattr(a, "max_blocks_per_req", 2), sv.SPEC_EINVAL),  # 40 tokens need 3 pages
+    (lambda a: setattr(a, "softmax_scale", -1.0), sv.SPEC_EINVAL),
+    (lambda a: setattr(a, "qkv_dtype", 5), sv.SPEC_EINVAL),
+    (lambda a: setattr(a, "block_size", 32), sv.SPEC_EUNSUPPORTED),
+    (lambda a: setattr(a, "d", 96), sv.SPEC_EUNSUPPORTED),
+    (lambda a: setattr(a, "qkv_dtype", sv.SPEC_F32), sv.SPEC_EUNSUPPORTED),  # fp32 in the bf16-only layout
+])
+def test_validate_attn_rejects(mutate, status):
+    a = _attn()
+    mutate(a)
+    assert sv.spec_validate_attn(a) == status
+    # the launching entry point reports the same status without touching the GPU
+    assert sv.lib().spec_verify_attn(C.byref(a), FAKE, 1 << 30, None) == status
+
+
+def test_validate_attn_per_request_limits():
+    assert sv.spec_validate_attn(_attn(kv_len=(40, 1), q_len=(3, 2))) == sv.SPEC_EINVAL      # kv_len < q_len
+    assert sv.spec_validate_attn(_attn(kv_len=(40, 20), q_len=(10, 2))) == sv.SPEC_EINVAL    # k_b > K_MAX
+    assert sv.spec_validate_attn(_attn(kv_len=(40, 20), q_len=(9, 1))) == sv.SPEC_OK
+
+
+def test_validate_reject():
+    assert sv.spec_validate_reject(_reject()) == sv.SPEC_OK
+    r = _reject()
+    r.counters = None
+    assert sv.spec_validate_reject(r) == sv.SPEC_EINVAL
+    r = _reject()
+    r.draft_logits = None
+    assert sv.spec_validate_reject(r) == sv.SPEC_EINVAL
+    r = _reject(q_len=(1, 1))       # k = 0 everywhere: no draft rows needed
+    r.draft_logits = None
+    r.draft_tokens = None
+    assert sv.spec_validate_reject(r) == sv.SPEC_OK
+    assert sv.spec_validate_reject(_reject(V=30)) == sv.SPEC_EUNSUPPORTED
+    assert sv.spec_validate_reject(_reject(q_len=(10, 2))) == sv.SPEC_EINVAL
+    r = _reject()
+    r.target_logits = FAKE + 4
+    assert sv.spec_validate_reject(r) == sv.SPEC_EINVAL
+
+
+def test_workspace_query_and_workspace_errors():
+    a, r = _attn(), _reject()
+    na = sv.spec_verify_workspace_bytes(a, None)
+    nr = sv.spec_verify_workspace_bytes(None, r)
+    nb = sv.spec_verify_workspace_bytes(a, r)
+    assert na > 0 and nr > 0 and nb == na + nr and na % 256 == 0 and nr % 256 == 0
+    L = sv.lib()
+    assert L.spec_verify_attn(C.byref(a), None, na, None) == sv.SPEC_EWORKSPACE
+    assert L.spec_verify_attn(C.byref(a), FAKE, na - 1, None) == sv.SPEC_EWORKSPACE
+    assert L.spec_verify_attn(C.byref(a), FAKE + 8, na, None) == sv.SPEC_EWORKSPACE      # misaligned
+    assert L.spec_reject_sample(C.byref(r), FAKE, nr - 1, None) == sv.SPEC_EWORKSPACE
+    assert L.spec_verify_step(C.byref(a), C.byref(r), FAKE, nb - 1, None) == sv.SPEC_EWORKSPACE
+    bad = _attn()
+    bad.q = None
+    with pytest.raises(sv.SpecVerifyError):
+        sv.spec_verify_workspace_bytes(bad, None)
+    # step: the two halves must describe the same batch
+    r3 = _reject(B=2, q_len=(2, 2))
+    assert L.spec_verify_step(C.byref(a), C.byref(r3), FAKE, 1 << 30, None) == sv.SPEC_EINVAL
+
+
+def test_repack_validation():
+    L = sv.lib()
+    assert L.spec_kv_repack_mfma(None, FAKE, FAKE + 256, FAKE + 512, 1, 1, 128, None) == sv.SPEC_EINVAL
+    assert L.spec_kv_repack_mfma(FAKE, FAKE + 256, FAKE, FAKE + 512, 1, 1, 128, None) == sv.SPEC_EINVAL   # aliasing
+    assert L.spec_kv_repack_mfma(FAKE, FAKE + 256, FAKE + 512, FAKE + 768, 1, 1, 96, None) == sv.SPEC_EUNSUPPORTED
+
+
+def test_product_never_touches_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2406_14066_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text and "spec_oracle" not in text, f
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".c")):
+            text = open(os.path.join(ROOT, "oracle", f)).read()
+            assert "paper_2406_14066_amd" not in text and "spec_verify.h" not in text, f
