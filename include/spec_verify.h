@@ -60,12 +60,15 @@ typedef enum { SPEC_F32 = 0, SPEC_BF16 = 1 } spec_dtype;
  * of one request for all KV heads; logical token t of request b is in page
  * block_table[b][t / 16], slot t % 16.
  *   SPEC_KV_TOKEN_MAJOR: K and V are [num_blocks][Hkv][16][d].
- *   SPEC_KV_MFMA: bf16 only.  K is [num_blocks][Hkv][d/8][16][8] (eight
- *     consecutive head dims of one token are 16 contiguous bytes, the 16
- *     tokens of a page follow each other), V is [num_blocks][Hkv][d][16]
- *     (the 16 tokens of one head dim are 32 contiguous bytes).  Both are the
- *     operand order of the gfx950 matrix instructions, so a wavefront loads a
- *     page with fully coalesced 16- and 8-byte-per-lane reads.
+ *   SPEC_KV_MFMA: bf16 only; both pools are tiled in the operand order of the
+ *     gfx950 matrix instructions, so that each 16-byte-per-lane load of a
+ *     wavefront is one contiguous 1 KB burst.
+ *     K is [num_blocks][Hkv][d/8][16 tokens][8 dims]: element (token s, dim c)
+ *       of a (page, head) is at (c/8)*128 + s*8 + c%8.
+ *     V is [num_blocks][Hkv][d/32][4 token groups][16 dims][2 dim halves][4 tokens]:
+ *       element (token s, dim c) is at
+ *       ((((c/32)*4 + s/4)*16 + c%16)*2 + (c/16)%2)*4 + s%4.
+ *     spec_kv_repack_mfma converts a token-major pool.
  */
 typedef enum { SPEC_KV_TOKEN_MAJOR = 0, SPEC_KV_MFMA = 1 } spec_kv_layout;
 

@@ -324,7 +324,8 @@ int oracle_reject_sample(int32_t B, int32_t V, const float *target_logits,
             for (int v = 0; v < V; ++v) {
                 if (v == best) continue;
                 const double e = -log(oracle_u_race(seed, step, b, v));
-                const double s = (r[v] > 0.0) ? r[v] / e : 0.0;
+                /* signed score: a loser with p < q needs its p - q perturbed past 0 before it can win */
+                const double s = (correction ? p[v] - q[v] : p[v]) / e;
                 const double w = (correction ? p[v] + q[v] : p[v]) / e;
                 double g;
                 if (isinf(best_score)) g = isinf(s) ? 0.0 : INFINITY;

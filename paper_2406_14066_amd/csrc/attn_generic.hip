@@ -37,11 +37,18 @@ __device__ __forceinline__ size_t k_index(int layout, int page, int Hkv, int kvh
     return ((head * (d >> 3) + (c >> 3)) * SPEC_BLOCK_SIZE + slot) * 8 + (c & 7);
 }
 
+// SPEC_KV_MFMA value layout inside one (page, kv head): [d/32][4 token groups][16 dims][2 dim halves][4 tokens]
+__device__ __forceinline__ size_t v_tiled_offset(int c, int slot)
+{
+    const int pair = c >> 5, half = (c >> 4) & 1, m = c & 15, g = slot >> 2, r = slot & 3;
+    return (size_t)((((pair * 4 + g) * 16 + m) * 2 + half) * 4 + r);
+}
+
 __device__ __forceinline__ size_t v_index(int layout, int page, int Hkv, int kvh, int slot, int c, int d)
 {
     const size_t head = (size_t)page * Hkv + kvh;
     if (layout == SPEC_KV_TOKEN_MAJOR) return (head * SPEC_BLOCK_SIZE + slot) * d + c;
-    return (head * d + c) * SPEC_BLOCK_SIZE + slot;
+    return head * d * SPEC_BLOCK_SIZE + v_tiled_offset(c, slot);
 }
 
 // request that owns packed query row `row`: largest b with cu_q_len[b] <= row
@@ -167,7 +174,7 @@ __global__ void kv_repack_kernel(const uint16_t *src_k, const uint16_t *src_v, u
     const size_t src = (head * SPEC_BLOCK_SIZE + slot) * d + (size_t)g * 8;
     const uint4 kk = *reinterpret_cast<const uint4 *>(src_k + src);
     *reinterpret_cast<uint4 *>(dst_k + ((head * groups + g) * SPEC_BLOCK_SIZE + slot) * 8) = kk;
-    for (int e = 0; e < 8; ++e) dst_v[(head * d + g * 8 + e) * SPEC_BLOCK_SIZE + slot] = src_v[src + e];
+    for (int e = 0; e < 8; ++e) dst_v[head * d * SPEC_BLOCK_SIZE + v_tiled_offset(g * 8 + e, slot)] = src_v[src + e];
 }
 
 }  // namespace

@@ -92,7 +92,7 @@ AttnPlan plan_attn(const spec_attn_args *a)
         int64_t chunk = (total * a->Hkv + target_blocks - 1) / target_blocks;
         chunk = (chunk + 63) / 64 * 64;
         if (chunk < 64) chunk = 64;
-        if (chunk > 4096) chunk = 4096;
+        if (chunk > 1024) chunk = 1024;  // a chunk's block-table slice is held one entry per lane
         pl.chunk_tokens = (int32_t)chunk;
     } else {
         pl.chunk_tokens = 256;  // one key per thread of the generic kernel
