@@ -1,0 +1,208 @@
+#!/usr/bin/env python3
+"""Benchmark of the speculative-verification step on one MI355X.
+
+A "step" is one pass of the whole hot path -- lookahead attention over the paged KV
+cache, then rejection sampling with bonus token -- over one batch of seeded synthetic
+input that is already resident in HBM.  The default workload is the Llama-2-7B-shaped
+single-layer verify (B=8, L=2048, k=4, 32/32 heads, d=128, bf16 paged KV, V=32000).
+
+KV pools and logits are rotated over several device copies so that consecutive steps
+do not find their inputs in the 256 MB last-level cache.
+
+Prints ONE JSON line:
+  value      verified token positions per second, sum_b (k_b+1) / t_step
+  roofline   achieved HBM rate of the dominant kernel (attention over the KV cache):
+             algorithmic bytes per launch / mean launch duration measured with HIP
+             events inside the timed region, against the 8 TB/s peak
+  cpu_baseline  the CPU oracle timed in this same run on this host
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5"])
+    ap.add_argument("--k", type=int, default=None, help="speculation length of the c3 sweep point")
+    ap.add_argument("--alpha", type=float, default=None, help="acceptance level of the c3 sweep point")
+    ap.add_argument("--rotate", type=int, default=0, help="device copies of KV/logits to cycle through (0 = auto)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-events", action="store_true",
+                    help="time the steps without per-kernel events (roofline then comes from a second loop)")
+    return ap.parse_args()
+
+
+def traffic_from_profile(workload):
+    """HBM bytes per attention launch measured with rocprofv3 counters, if a summary is committed."""
+    path = os.path.join(ROOT, "profiles", "attn_mfma_%s_pmc.txt" % workload)
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the step has no multi-GPU path); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2406_14066_amd import workloads as W
+    from paper_2406_14066_amd import spec_verify as sv
+    from paper_2406_14066_amd.harness import DeviceStep
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    sv.lib()  # fail loudly if the HIP library is missing
+
+    kw = {}
+    if args.workload == "c3":
+        kw = dict(k=args.k, alpha=args.alpha)
+    w = W.config(args.workload, **kw)
+    ds = DeviceStep(w, kv_layout=sv.KV_MFMA, with_debug=False)
+
+    attn_bytes = w.attn_algorithmic_bytes()
+    rej_bytes = w.reject_algorithmic_bytes()
+    step_bytes = attn_bytes + rej_bytes
+    kv_bytes = 2 * ds.k_cache.numel() * ds.k_cache.element_size()
+    nrot = args.rotate or max(2, int(np.ceil(1.2e9 / max(kv_bytes + rej_bytes, 1))))
+    nrot = min(nrot, 16)
+
+    # rotated copies: same bytes at different addresses
+    variants = []
+    for i in range(nrot):
+        if i == 0:
+            variants.append((ds.attn_args, ds.reject_args, None))
+            continue
+        kc, vc = ds.k_cache.clone(), ds.v_cache.clone()
+        tl = ds.target_logits.clone()
+        dl = ds.draft_logits.clone() if ds.draft_logits is not None else None
+        a, ka = sv.make_attn_args(ds.q, kc, vc, ds.block_table, ds.kv_len, ds.cu_q_len, ds.out, w.kv_len,
+                                  w.cu_q_len, Hkv=w.Hkv, kv_layout=sv.KV_MFMA)
+        r, kr = sv.make_reject_args(tl, dl, ds.draft_tokens, ds.cu_q_len, w.cu_q_len, ds.accepted_len,
+                                    ds.next_token, ds.counters, philox_seed=w.philox_seed,
+                                    philox_step=w.philox_step, out_tokens=ds.out_tokens)
+        variants.append((a, r, (ka, kr)))
+
+    stream = torch.cuda.current_stream()
+
+    def run(n, first=0):
+        for i in range(n):
+            a, r, _ = variants[(first + i) % nrot]
+            sv.spec_verify_step(a, r, ds.workspace, stream)
+
+    run(args.warmup)
+    torch.cuda.synchronize()
+
+    events_in_region = not args.no_kernel_events
+    if events_in_region:
+        sv.spec_profile_begin(4 * args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(args.steps, first=args.warmup)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    if events_in_region:
+        kt = sv.spec_profile_end()
+    else:
+        sv.spec_profile_begin(4 * args.steps)
+        run(args.steps, first=args.warmup)
+        torch.cuda.synchronize()
+        kt = sv.spec_profile_end()
+
+    sec_per_step = (t1 - t0) / args.steps
+    value = w.verified_tokens() / sec_per_step
+    res = ds.results()
+    emitted_per_step = int(res["counters"][3]) // max(int(res["counters"][5]) // w.B, 1)
+
+    kernel_us = {k: (1e3 * ms / n if n else None) for k, (ms, n) in kt.items()}
+    attn_us = kernel_us["attn_partial"]
+    achieved = attn_bytes / (attn_us * 1e-6) / 1e9
+    traffic = traffic_from_profile(args.workload)
+
+    out = {
+        "metric": "verified tokens/s per MI355X for spec-verify step",
+        "value": value,
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": sec_per_step * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {
+            "workload": "%s: B=%d, L=%s, k=%s, Hq/Hkv=%d/%d, d=%d, bf16 paged KV (block 16, shuffled table), V=%d fp32 logits"
+                        % (w.name, w.B, _span(w.kv_len), _span(w.k), w.Hq, w.Hkv, w.d, w.V),
+            "kv_layout": "mfma-tiled pages",
+            "rotated_copies": nrot,
+            "verified_tokens_per_step": w.verified_tokens(),
+            "emitted_tokens_per_step": emitted_per_step,
+            "goodput_tokens_per_s": emitted_per_step / sec_per_step,
+        },
+        "step_hbm": {
+            "algorithmic_bytes": step_bytes,
+            "achieved_GBps": step_bytes / sec_per_step / 1e9,
+            "frac_of_peak": step_bytes / sec_per_step / 1e9 / HBM_PEAK_GBS,
+        },
+        "kernel_us": kernel_us,
+        "roofline": {
+            "kernel": "attn_mfma_kernel (attention over one KV chunk)",
+            "bound": "hbm",
+            "achieved": achieved,
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS,
+            "traffic": traffic,
+            "algorithmic_bytes_per_launch": attn_bytes,
+            "events_in_timed_region": events_in_region,
+        },
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        t2 = time.perf_counter()
+        oracle.verify_attn(w.q, w.k_pages, w.v_pages, w.block_table, w.kv_len, w.cu_q_len)
+        t3 = time.perf_counter()
+        oracle.reject_sample(w.target_logits, w.draft_logits, w.draft_tokens, w.cu_q_len, w.philox_seed,
+                             w.philox_step)
+        t4 = time.perf_counter()
+        out["cpu_baseline"] = {
+            "value": w.verified_tokens() / (t4 - t2),
+            "unit": "tokens/s",
+            "cores": 1,
+            "kind": "oracle",
+            "sample": "the whole %s step once (attention %.2f s + rejection sampling %.2f s), single thread; host has %d cpus"
+                      % (w.name, t3 - t2, t4 - t3, os.cpu_count()),
+        }
+    print(json.dumps(out))
+
+
+def _span(a):
+    a = np.asarray(a)
+    return str(int(a[0])) if (a == a[0]).all() else "%d..%d" % (a.min(), a.max())
+
+
+if __name__ == "__main__":
+    main()

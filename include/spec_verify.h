@@ -163,6 +163,23 @@ spec_status spec_validate_reject(const spec_reject_args *reject);
 spec_status spec_kv_repack_mfma(const void *src_k, const void *src_v, void *dst_k, void *dst_v,
                                 int32_t num_blocks, int32_t Hkv, int32_t d, void *hip_stream);
 
+/*
+ * Measurement aid (not part of the step): per-kernel GPU time from HIP events.
+ * Between spec_profile_begin and spec_profile_end every kernel the library
+ * launches (up to max_launches of them) is bracketed by two event records on
+ * the launch stream.  spec_profile_end waits for those events and returns, per
+ * kernel id, the summed duration in milliseconds and the number of launches
+ * (both arrays have SPEC_NUM_KERNELS entries).  begin creates the events, so
+ * it must not be called during stream capture; the pair is not thread safe.
+ */
+#define SPEC_NUM_KERNELS 4
+#define SPEC_KERNEL_ATTN_PARTIAL 0  /* attention over one KV chunk (matrix-instruction or generic kernel) */
+#define SPEC_KERNEL_ATTN_COMBINE 1  /* merge of the chunk partials */
+#define SPEC_KERNEL_LOGIT_STATS 2   /* per-row softmax statistics */
+#define SPEC_KERNEL_ACCEPT_RACE 3   /* accept chain + race for the next token */
+spec_status spec_profile_begin(int32_t max_launches);
+spec_status spec_profile_end(float *total_ms, int32_t *launches);
+
 const char *spec_status_string(spec_status status);
 
 /* Library version: major * 10000 + minor * 100 + patch. */

@@ -6,11 +6,39 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <vector>
+
 namespace specv {
 
 namespace {
 
 constexpr size_t kAlign = 256;
+
+// Optional per-kernel timing with HIP events (spec_profile_begin / spec_profile_end).
+// Off by default; when on, every kernel launch is bracketed by two event records on
+// the launch stream.  Not thread safe; meant for the benchmark.
+struct KernelProfiler {
+    bool on = false;
+    std::vector<hipEvent_t> events;   // pairs: start, stop
+    std::vector<int> kernel_of_pair;
+    size_t capacity_pairs = 0;
+};
+KernelProfiler g_prof;
+
+template <typename F>
+hipError_t timed(int kernel_id, hipStream_t stream, F launch)
+{
+    const bool rec = g_prof.on && g_prof.kernel_of_pair.size() < g_prof.capacity_pairs;
+    size_t pair = 0;
+    if (rec) {
+        pair = g_prof.kernel_of_pair.size();
+        g_prof.kernel_of_pair.push_back(kernel_id);
+        (void)hipEventRecord(g_prof.events[2 * pair], stream);
+    }
+    const hipError_t err = launch();
+    if (rec) (void)hipEventRecord(g_prof.events[2 * pair + 1], stream);
+    return err;
+}
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 spec_status validate_attn(const spec_attn_args *a)
@@ -93,6 +121,12 @@ AttnPlan plan_attn(const spec_attn_args *a)
         chunk = (chunk + 63) / 64 * 64;
         if (chunk < 64) chunk = 64;
         if (chunk > 1024) chunk = 1024;  // a chunk's block-table slice is held one entry per lane
+        // tuning switch: SPEC_VERIFY_CHUNK=<tokens, multiple of 64, <= 1024> overrides the heuristic
+        const char *forced = getenv("SPEC_VERIFY_CHUNK");
+        if (forced != nullptr) {
+            const long v = strtol(forced, nullptr, 10);
+            if (v >= 64 && v <= 1024 && v % 64 == 0) chunk = v;
+        }
         pl.chunk_tokens = (int32_t)chunk;
     } else {
         pl.chunk_tokens = 256;  // one key per thread of the generic kernel
@@ -161,9 +195,11 @@ spec_status run_attn(const spec_attn_args *a, const AttnPlan &pl, char *ws, hipS
     p.out = a->out;
     p.ws_acc = reinterpret_cast<float *>(ws);
     p.ws_ml = reinterpret_cast<float *>(ws + pl.acc_bytes);
-    hipError_t err = pl.use_mfma ? launch_attn_mfma(p, pl.row_tiles, stream) : launch_attn_generic(p, a->qkv_dtype, stream);
+    hipError_t err = timed(SPEC_KERNEL_ATTN_PARTIAL, stream, [&] {
+        return pl.use_mfma ? launch_attn_mfma(p, pl.row_tiles, stream) : launch_attn_generic(p, a->qkv_dtype, stream);
+    });
     if (err != hipSuccess) return SPEC_EHIP;
-    err = launch_attn_combine(p, stream);
+    err = timed(SPEC_KERNEL_ATTN_COMBINE, stream, [&] { return launch_attn_combine(p, stream); });
     return err == hipSuccess ? SPEC_OK : SPEC_EHIP;
 }
 
@@ -186,9 +222,9 @@ spec_status run_reject(const spec_reject_args *r, const RejectPlan &pl, char *ws
     p.stats = reinterpret_cast<RowStat *>(ws + pl.stats_off);
     p.race_partial = reinterpret_cast<unsigned long long *>(ws + pl.race_off);
     p.tickets = reinterpret_cast<int32_t *>(ws + pl.ticket_off);
-    hipError_t err = launch_logit_stats(p, stream);
+    hipError_t err = timed(SPEC_KERNEL_LOGIT_STATS, stream, [&] { return launch_logit_stats(p, stream); });
     if (err != hipSuccess) return SPEC_EHIP;
-    err = launch_accept_race(p, stream);
+    err = timed(SPEC_KERNEL_ACCEPT_RACE, stream, [&] { return launch_accept_race(p, stream); });
     return err == hipSuccess ? SPEC_OK : SPEC_EHIP;
 }
 
@@ -267,6 +303,43 @@ spec_status spec_kv_repack_mfma(const void *src_k, const void *src_v, void *dst_
     const hipError_t err = launch_kv_repack(src_k, src_v, dst_k, dst_v, num_blocks, Hkv, d,
                                             static_cast<hipStream_t>(hip_stream));
     return err == hipSuccess ? SPEC_OK : SPEC_EHIP;
+}
+
+spec_status spec_profile_begin(int32_t max_launches)
+{
+    if (max_launches < 1 || max_launches > (1 << 20)) return SPEC_EINVAL;
+    if (g_prof.on) return SPEC_EINVAL;
+    g_prof.events.assign(2 * (size_t)max_launches, nullptr);
+    for (auto &e : g_prof.events)
+        if (hipEventCreate(&e) != hipSuccess) return SPEC_EHIP;
+    g_prof.kernel_of_pair.clear();
+    g_prof.kernel_of_pair.reserve(max_launches);
+    g_prof.capacity_pairs = (size_t)max_launches;
+    g_prof.on = true;
+    return SPEC_OK;
+}
+
+spec_status spec_profile_end(float *total_ms, int32_t *launches)
+{
+    if (!g_prof.on || total_ms == nullptr || launches == nullptr) return SPEC_EINVAL;
+    g_prof.on = false;
+    for (int i = 0; i < SPEC_NUM_KERNELS; ++i) { total_ms[i] = 0.0f; launches[i] = 0; }
+    spec_status st = SPEC_OK;
+    for (size_t pair = 0; pair < g_prof.kernel_of_pair.size(); ++pair) {
+        float ms = 0.0f;
+        if (hipEventSynchronize(g_prof.events[2 * pair + 1]) != hipSuccess ||
+            hipEventElapsedTime(&ms, g_prof.events[2 * pair], g_prof.events[2 * pair + 1]) != hipSuccess) {
+            st = SPEC_EHIP;
+            break;
+        }
+        total_ms[g_prof.kernel_of_pair[pair]] += ms;
+        launches[g_prof.kernel_of_pair[pair]] += 1;
+    }
+    for (auto &e : g_prof.events) (void)hipEventDestroy(e);
+    g_prof.events.clear();
+    g_prof.kernel_of_pair.clear();
+    g_prof.capacity_pairs = 0;
+    return st;
 }
 
 const char *spec_status_string(spec_status status)

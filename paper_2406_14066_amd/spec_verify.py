@@ -54,8 +54,10 @@ class RejectArgs(C.Structure):
 EXPORTS = (
     "spec_verify_workspace_bytes", "spec_verify_attn", "spec_reject_sample", "spec_verify_step",
     "spec_validate_attn", "spec_validate_reject", "spec_kv_repack_mfma", "spec_status_string",
-    "spec_verify_version",
+    "spec_verify_version", "spec_profile_begin", "spec_profile_end",
 )
+NUM_KERNELS = 4
+KERNEL_NAMES = ("attn_partial", "attn_combine", "logit_stats", "accept_race")
 
 _lib = None
 
@@ -91,6 +93,10 @@ def lib():
         L.spec_kv_repack_mfma.restype = C.c_int
         L.spec_status_string.argtypes = [C.c_int]
         L.spec_status_string.restype = C.c_char_p
+        L.spec_profile_begin.argtypes = [C.c_int32]
+        L.spec_profile_begin.restype = C.c_int
+        L.spec_profile_end.argtypes = [C.c_void_p, C.c_void_p]
+        L.spec_profile_end.restype = C.c_int
         L.spec_verify_version.argtypes = []
         L.spec_verify_version.restype = C.c_int32
         _lib = L
@@ -213,6 +219,18 @@ def spec_kv_repack_mfma(src_k, src_v, dst_k, dst_v, stream=None) -> None:
     assert bs == BLOCK_SIZE and src_k.element_size() == 2
     _check(lib().spec_kv_repack_mfma(src_k.data_ptr(), src_v.data_ptr(), dst_k.data_ptr(), dst_v.data_ptr(),
                                      nb, Hkv, d, _stream_handle(stream)), "spec_kv_repack_mfma")
+
+
+def spec_profile_begin(max_launches: int) -> None:
+    _check(lib().spec_profile_begin(int(max_launches)), "spec_profile_begin")
+
+
+def spec_profile_end():
+    """Returns {kernel name: (total ms, launches)}."""
+    ms = (C.c_float * NUM_KERNELS)()
+    n = (C.c_int32 * NUM_KERNELS)()
+    _check(lib().spec_profile_end(ms, n), "spec_profile_end")
+    return {KERNEL_NAMES[i]: (float(ms[i]), int(n[i])) for i in range(NUM_KERNELS)}
 
 
 def spec_verify_version() -> int:
