@@ -11,7 +11,7 @@ do not find their inputs in the 256 MB last-level cache.
 
 Prints ONE JSON line:
   value      verified token positions per second, sum_b (k_b+1) / t_step
-  roofline   achieved HBM rate of the dominant kernel (attention over the KV cache):
+  roofline   achieved HBM rate of the step's kernel (the whole step is one launch):
              algorithmic bytes per launch / mean launch duration measured with HIP
              events inside the timed region, against the 8 TB/s peak
   cpu_baseline  the CPU oracle timed in this same run on this host
@@ -47,7 +47,7 @@ def parse():
 
 def traffic_from_profile(workload):
     """HBM bytes per attention launch measured with rocprofv3 counters, if a summary is committed."""
-    path = os.path.join(ROOT, "profiles", "attn_mfma_%s_pmc.txt" % workload)
+    path = os.path.join(ROOT, "profiles", "spec_step_kernel_%s_pmc.txt" % workload)
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch:"):
@@ -115,7 +115,7 @@ def main():
 
     events_in_region = not args.no_kernel_events
     if events_in_region:
-        sv.spec_profile_begin(4 * args.steps)
+        sv.spec_profile_begin(args.steps)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     run(args.steps, first=args.warmup)
@@ -124,7 +124,7 @@ def main():
     if events_in_region:
         kt = sv.spec_profile_end()
     else:
-        sv.spec_profile_begin(4 * args.steps)
+        sv.spec_profile_begin(args.steps)
         run(args.steps, first=args.warmup)
         torch.cuda.synchronize()
         kt = sv.spec_profile_end()
@@ -135,8 +135,8 @@ def main():
     emitted_per_step = int(res["counters"][3]) // max(int(res["counters"][5]) // w.B, 1)
 
     kernel_us = {k: (1e3 * ms / n if n else None) for k, (ms, n) in kt.items()}
-    attn_us = kernel_us["attn_partial"]
-    achieved = attn_bytes / (attn_us * 1e-6) / 1e9
+    step_us = kernel_us["step"]
+    achieved = step_bytes / (step_us * 1e-6) / 1e9
     traffic = traffic_from_profile(args.workload)
 
     out = {
@@ -168,14 +168,16 @@ def main():
         },
         "kernel_us": kernel_us,
         "roofline": {
-            "kernel": "attn_mfma_kernel (attention over one KV chunk)",
+            "kernel": "spec_step_kernel (whole step in one launch: attention over the paged KV cache + rejection sampling)",
             "bound": "hbm",
             "achieved": achieved,
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
             "traffic": traffic,
-            "algorithmic_bytes_per_launch": attn_bytes,
+            "algorithmic_bytes_per_launch": step_bytes,
+            "attention_bytes": attn_bytes,
+            "rejection_bytes": rej_bytes,
             "events_in_timed_region": events_in_region,
         },
     }

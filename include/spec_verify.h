@@ -172,11 +172,12 @@ spec_status spec_kv_repack_mfma(const void *src_k, const void *src_v, void *dst_
  * (both arrays have SPEC_NUM_KERNELS entries).  begin creates the events, so
  * it must not be called during stream capture; the pair is not thread safe.
  */
-#define SPEC_NUM_KERNELS 4
-#define SPEC_KERNEL_ATTN_PARTIAL 0  /* attention over one KV chunk (matrix-instruction or generic kernel) */
-#define SPEC_KERNEL_ATTN_COMBINE 1  /* merge of the chunk partials */
-#define SPEC_KERNEL_LOGIT_STATS 2   /* per-row softmax statistics */
-#define SPEC_KERNEL_ACCEPT_RACE 3   /* accept chain + race for the next token */
+#define SPEC_NUM_KERNELS 5
+#define SPEC_KERNEL_STEP 0          /* the whole step in one launch (attention + rejection sampling) */
+#define SPEC_KERNEL_ATTN 1          /* attention-only launch of the matrix-instruction kernel */
+#define SPEC_KERNEL_ATTN_GENERIC 2  /* generic attention over one KV chunk (fp32 / token-major path) */
+#define SPEC_KERNEL_ATTN_COMBINE 3  /* merge of the generic kernel's chunk partials */
+#define SPEC_KERNEL_REJECT 4        /* rejection-sampling-only launch */
 spec_status spec_profile_begin(int32_t max_launches);
 spec_status spec_profile_end(float *total_ms, int32_t *launches);
 

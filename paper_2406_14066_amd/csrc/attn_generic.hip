@@ -148,10 +148,13 @@ __global__ void attn_combine_kernel(AttnParams p)
     const int tid = threadIdx.x;
     const int b = find_request(p.cu_q_len, p.B, row);
     const int nchunks = (p.kv_len[b] + p.chunk_tokens - 1) / p.chunk_tokens;
+    if (nchunks == 1 && p.single_chunk_direct) return;
     const size_t base = ((size_t)row * p.Hq + h) * p.max_chunks;
     float mx = kEmptyMax;
+#pragma unroll 8
     for (int c = 0; c < nchunks; ++c) mx = fmaxf(mx, p.ws_ml[(base + c) * 2]);
     float denom = 0.0f, acc = 0.0f;
+#pragma unroll 8
     for (int c = 0; c < nchunks; ++c) {
         const float w = __builtin_amdgcn_exp2f(p.ws_ml[(base + c) * 2] - mx);
         denom = fmaf(w, p.ws_ml[(base + c) * 2 + 1], denom);

@@ -16,19 +16,25 @@ constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kEmptyMax = -1.0e30f;  // running maximum of a row that has seen no key yet
 
 // ---------------------------------------------------------------- attention
-// Split of the KV length: every request is cut into chunks of `chunk_tokens`
-// tokens; chunk c of a request covers tokens [c*chunk, min((c+1)*chunk, kv_len)).
-// Each (query row, query head, chunk) owns one partial result in the workspace:
-//   acc  [T*Hq][max_chunks][d]  un-normalised sum_t exp(s_t - m) V_t
-//   ml   [T*Hq][max_chunks][2]  running maximum m and sum l of exp(s_t - m)
+// Split of the KV length.  A request of L tokens is cut into
+// nch = ceil(L / chunk_tokens) chunks.  The generic kernel uses chunks of exactly
+// chunk_tokens; the matrix-instruction kernel evens them out per request
+// (chunk = ceil(L / nch) rounded up to 64 tokens).  Each (query row, query head,
+// chunk) owns one partial result in the workspace:
+//   acc  [T*Hq][max_chunks][d]  un-normalised sum_t 2^(s_t - m) V_t
+//   ml   [T*Hq][max_chunks][2]  running maximum m (base-2 units) and sum l of 2^(s_t - m)
+// tickets [B*Hkv] count the chunks of a (request, KV head) that have finished;
+// the block that finishes last merges the partials (matrix-instruction kernel).
 struct AttnPlan {
     int32_t chunk_tokens;
     int32_t max_chunks;
     int32_t max_q_len;
     int32_t use_mfma;      // 1: bf16 matrix-instruction kernel, 0: generic kernel
     int32_t row_tiles;     // 16-row tiles covering max_q_len * (Hq/Hkv) rows (mfma kernel)
+    int32_t fused_combine; // mfma kernel merges the chunk partials itself (few chunks) or leaves it to the combine kernel
     size_t acc_bytes;
     size_t ml_bytes;
+    size_t ticket_bytes;
     size_t total_bytes;
 };
 
@@ -42,27 +48,24 @@ struct AttnParams {
     float *out;
     float *ws_acc;
     float *ws_ml;
+    unsigned long long *tickets;
+    uint32_t generation;  // tags this call's ticket values, never 0
+    int32_t fused_combine;        // matrix kernel: the last chunk's block merges the partials (needs max_chunks <= 16)
+    int32_t single_chunk_direct;  // requests with one chunk were written straight to `out`: the combine kernel skips them
 };
-
-hipError_t launch_attn_generic(const AttnParams &p, int dtype, hipStream_t stream);
-hipError_t launch_attn_mfma(const AttnParams &p, int row_tiles, hipStream_t stream);
-hipError_t launch_attn_combine(const AttnParams &p, hipStream_t stream);
-hipError_t launch_kv_repack(const void *src_k, const void *src_v, void *dst_k, void *dst_v, int32_t num_blocks,
-                            int32_t Hkv, int32_t d, hipStream_t stream);
 
 // ---------------------------------------------------------------- rejection
 struct RowStat {   // one vocabulary segment of one logit row
     double sum;    // sum_v 2^(x_v * log2(e) - off2)
     float off2;    // integer-valued base-2 offset, about max_v x_v * log2(e)
-    float pad;
+    uint32_t tag;  // generation of the call that wrote it, 0 = empty
 };
 
 struct RejectPlan {
-    int32_t stat_segments, stat_seg_len;   // segments per row in the statistics pass
-    int32_t race_segments, race_seg_len;   // blocks per request in the race pass
-    size_t stats_off, stats_bytes;
-    size_t race_off, race_bytes;
-    size_t ticket_off, ticket_bytes;
+    int32_t stat_segments, stat_seg_len;   // vocabulary segments per row in the statistics pass
+    int32_t race_segments, race_seg_len;   // vocabulary segments per request in the race
+    size_t stats_off, stats_bytes;         // RowStat [rows][stat_segments]
+    size_t partial_off, partial_bytes;     // race partials [B][race_segments][2]
     size_t total_bytes;
 };
 
@@ -74,13 +77,22 @@ struct RejectParams {
     int32_t *accepted_len, *next_token, *out_tokens;
     unsigned long long *counters;
     double *debug_u_ratio;
-    int32_t stat_segments, stat_seg_len, race_segments, race_seg_len;
-    RowStat *stats;
-    unsigned long long *race_partial;
-    int32_t *tickets;
+    int32_t stat_segments, stat_seg_len;
+    int32_t race_segments, race_seg_len;
+    int32_t spin_limit;                  // polls a race block spends waiting for its request's accept phase
+    RowStat *stats;                      // [rows][stat_segments]; `tag` holds the generation once valid
+    unsigned long long *race_partial;    // [B][race_segments][2]: best (score, id) of a segment; generation tag
+    uint32_t generation;
 };
 
-hipError_t launch_logit_stats(const RejectParams &p, hipStream_t stream);
-hipError_t launch_accept_race(const RejectParams &p, hipStream_t stream);
+// One launch for the whole step (either half may be absent).  `attn` needs the
+// matrix-instruction path (bf16, SPEC_KV_MFMA, d = 128, row_tiles <= 3).
+hipError_t launch_step_fused(const AttnParams *attn, int row_tiles, const RejectParams *reject, hipStream_t stream);
+
+// Generic attention path: partial kernel + combine kernel.
+hipError_t launch_attn_generic(const AttnParams &p, int dtype, hipStream_t stream);
+hipError_t launch_attn_combine(const AttnParams &p, hipStream_t stream);
+hipError_t launch_kv_repack(const void *src_k, const void *src_v, void *dst_k, void *dst_v, int32_t num_blocks,
+                            int32_t Hkv, int32_t d, hipStream_t stream);
 
 }  // namespace specv

@@ -6,6 +6,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <atomic>
 #include <vector>
 
 namespace specv {
@@ -99,10 +100,8 @@ AttnPlan plan_attn(const spec_attn_args *a)
 {
     AttnPlan pl;
     memset(&pl, 0, sizeof pl);
-    int64_t total = 0;
     int max_len = 0, max_q = 0;
     for (int b = 0; b < a->B; ++b) {
-        total += a->host_kv_len[b];
         if (a->host_kv_len[b] > max_len) max_len = a->host_kv_len[b];
         const int q_len = a->host_cu_q_len[b + 1] - a->host_cu_q_len[b];
         if (q_len > max_q) max_q = q_len;
@@ -116,26 +115,35 @@ AttnPlan plan_attn(const spec_attn_args *a)
     const char *force = getenv("SPEC_VERIFY_FORCE_GENERIC");
     if (force != nullptr && force[0] == '1') pl.use_mfma = 0;
     if (pl.use_mfma) {
-        const int64_t target_blocks = 2048;
-        int64_t chunk = (total * a->Hkv + target_blocks - 1) / target_blocks;
-        chunk = (chunk + 63) / 64 * 64;
+        // one block per (request, KV head, chunk): split the longest request so that the launch
+        // has about `target_blocks` blocks, and not at all when the batch alone provides them
+        long target_blocks = 2048;
+        if (const char *t = getenv("SPEC_VERIFY_TARGET_BLOCKS")) {   // tuning switch
+            const long v = strtol(t, nullptr, 10);
+            if (v >= 1 && v <= (1 << 20)) target_blocks = v;
+        }
+        const int64_t units = (int64_t)a->B * a->Hkv;
+        int64_t nsplit = (target_blocks + units / 2) / units;
+        if (nsplit < 1) nsplit = 1;
+        int64_t chunk = (max_len + nsplit - 1) / nsplit;
+        chunk = (chunk + SPEC_BLOCK_SIZE - 1) / SPEC_BLOCK_SIZE * SPEC_BLOCK_SIZE;
         if (chunk < 64) chunk = 64;
-        if (chunk > 1024) chunk = 1024;  // a chunk's block-table slice is held one entry per lane
-        // tuning switch: SPEC_VERIFY_CHUNK=<tokens, multiple of 64, <= 1024> overrides the heuristic
-        const char *forced = getenv("SPEC_VERIFY_CHUNK");
-        if (forced != nullptr) {
+        if (chunk > 4096) chunk = 4096;  // a wavefront holds its pages' block-table entries one per lane
+        if (const char *forced = getenv("SPEC_VERIFY_CHUNK")) {      // tuning switch: tokens, multiple of 16
             const long v = strtol(forced, nullptr, 10);
-            if (v >= 64 && v <= 1024 && v % 64 == 0) chunk = v;
+            if (v >= 16 && v <= 4096 && v % SPEC_BLOCK_SIZE == 0) chunk = v;
         }
         pl.chunk_tokens = (int32_t)chunk;
     } else {
         pl.chunk_tokens = 256;  // one key per thread of the generic kernel
     }
     pl.max_chunks = (max_len + pl.chunk_tokens - 1) / pl.chunk_tokens;
+    pl.fused_combine = (pl.use_mfma && pl.max_chunks <= 16) ? 1 : 0;
     const size_t slots = (size_t)a->T * a->Hq * pl.max_chunks;
     pl.acc_bytes = align_up(slots * a->d * sizeof(float));
     pl.ml_bytes = align_up(slots * 2 * sizeof(float));
-    pl.total_bytes = pl.acc_bytes + pl.ml_bytes;
+    pl.ticket_bytes = align_up((size_t)a->B * a->Hkv * sizeof(unsigned long long));
+    pl.total_bytes = pl.acc_bytes + pl.ml_bytes + pl.ticket_bytes;
     return pl;
 }
 
@@ -144,9 +152,9 @@ RejectPlan plan_reject(const spec_reject_args *r, size_t base)
     RejectPlan pl;
     memset(&pl, 0, sizeof pl);
     const int rows = 2 * r->T - r->B;
-    // statistics pass: aim for >= 2048 blocks, segments of >= 1024 logits
-    int segs = (2048 + rows - 1) / rows;
-    const int max_by_len = (r->V + 1023) / 1024;
+    // statistics: about 512 blocks in all, segments of >= 4096 logits, at most 32 per row
+    int segs = (512 + rows - 1) / rows;
+    const int max_by_len = (r->V + 4095) / 4096;
     if (segs > max_by_len) segs = max_by_len;
     if (segs > 32) segs = 32;
     if (segs < 1) segs = 1;
@@ -154,9 +162,10 @@ RejectPlan plan_reject(const spec_reject_args *r, size_t base)
     seg_len = (seg_len + 3) / 4 * 4;
     pl.stat_seg_len = seg_len;
     pl.stat_segments = (r->V + seg_len - 1) / seg_len;
-    // race pass: aim for >= 1024 blocks, segments of >= 1024 vocabulary ids
+    // race: about 1024 blocks in all, segments of >= 1024 vocabulary ids, at most 64 per request
     int rsegs = (1024 + r->B - 1) / r->B;
-    if (rsegs > max_by_len) rsegs = max_by_len;
+    const int rmax_by_len = (r->V + 1023) / 1024;
+    if (rsegs > rmax_by_len) rsegs = rmax_by_len;
     if (rsegs > 64) rsegs = 64;
     if (rsegs < 1) rsegs = 1;
     int rlen = (r->V + rsegs - 1) / rsegs;
@@ -166,12 +175,19 @@ RejectPlan plan_reject(const spec_reject_args *r, size_t base)
 
     pl.stats_off = base;
     pl.stats_bytes = align_up((size_t)rows * pl.stat_segments * sizeof(RowStat));
-    pl.race_off = pl.stats_off + pl.stats_bytes;
-    pl.race_bytes = align_up((size_t)r->B * pl.race_segments * sizeof(unsigned long long));
-    pl.ticket_off = pl.race_off + pl.race_bytes;
-    pl.ticket_bytes = align_up((size_t)r->B * sizeof(int32_t));
-    pl.total_bytes = pl.stats_bytes + pl.race_bytes + pl.ticket_bytes;
+    pl.partial_off = pl.stats_off + pl.stats_bytes;
+    pl.partial_bytes = align_up((size_t)r->B * pl.race_segments * 2 * sizeof(unsigned long long));
+    pl.total_bytes = pl.stats_bytes + pl.partial_bytes;
     return pl;
+}
+
+// Tag of a call's tickets (see step_kernel.hip); unique per call within the process, never 0.
+uint32_t next_generation()
+{
+    static std::atomic<uint32_t> counter{0x5EC0u};
+    uint32_t g = ++counter;
+    if (g == 0) g = ++counter;
+    return g;
 }
 
 spec_status check_workspace(void *ws, size_t have, size_t need)
@@ -180,7 +196,7 @@ spec_status check_workspace(void *ws, size_t have, size_t need)
     return SPEC_OK;
 }
 
-spec_status run_attn(const spec_attn_args *a, const AttnPlan &pl, char *ws, hipStream_t stream)
+AttnParams attn_params(const spec_attn_args *a, const AttnPlan &pl, char *ws)
 {
     AttnParams p;
     memset(&p, 0, sizeof p);
@@ -195,15 +211,14 @@ spec_status run_attn(const spec_attn_args *a, const AttnPlan &pl, char *ws, hipS
     p.out = a->out;
     p.ws_acc = reinterpret_cast<float *>(ws);
     p.ws_ml = reinterpret_cast<float *>(ws + pl.acc_bytes);
-    hipError_t err = timed(SPEC_KERNEL_ATTN_PARTIAL, stream, [&] {
-        return pl.use_mfma ? launch_attn_mfma(p, pl.row_tiles, stream) : launch_attn_generic(p, a->qkv_dtype, stream);
-    });
-    if (err != hipSuccess) return SPEC_EHIP;
-    err = timed(SPEC_KERNEL_ATTN_COMBINE, stream, [&] { return launch_attn_combine(p, stream); });
-    return err == hipSuccess ? SPEC_OK : SPEC_EHIP;
+    p.tickets = reinterpret_cast<unsigned long long *>(ws + pl.acc_bytes + pl.ml_bytes);
+    p.generation = next_generation();
+    p.fused_combine = pl.fused_combine;
+    p.single_chunk_direct = pl.use_mfma;
+    return p;
 }
 
-spec_status run_reject(const spec_reject_args *r, const RejectPlan &pl, char *ws, hipStream_t stream)
+RejectParams reject_params(const spec_reject_args *r, const RejectPlan &pl, char *ws)
 {
     RejectParams p;
     memset(&p, 0, sizeof p);
@@ -219,12 +234,18 @@ spec_status run_reject(const spec_reject_args *r, const RejectPlan &pl, char *ws
     p.debug_u_ratio = r->debug_u_ratio;
     p.stat_segments = pl.stat_segments; p.stat_seg_len = pl.stat_seg_len;
     p.race_segments = pl.race_segments; p.race_seg_len = pl.race_seg_len;
+    p.spin_limit = 1 << 20;   // about a second of polling; never reached in a healthy launch
     p.stats = reinterpret_cast<RowStat *>(ws + pl.stats_off);
-    p.race_partial = reinterpret_cast<unsigned long long *>(ws + pl.race_off);
-    p.tickets = reinterpret_cast<int32_t *>(ws + pl.ticket_off);
-    hipError_t err = timed(SPEC_KERNEL_LOGIT_STATS, stream, [&] { return launch_logit_stats(p, stream); });
+    p.race_partial = reinterpret_cast<unsigned long long *>(ws + pl.partial_off);
+    p.generation = next_generation();
+    return p;
+}
+
+spec_status run_attn_generic(const AttnParams &p, int dtype, hipStream_t stream)
+{
+    hipError_t err = timed(SPEC_KERNEL_ATTN_GENERIC, stream, [&] { return launch_attn_generic(p, dtype, stream); });
     if (err != hipSuccess) return SPEC_EHIP;
-    err = timed(SPEC_KERNEL_ACCEPT_RACE, stream, [&] { return launch_accept_race(p, stream); });
+    err = timed(SPEC_KERNEL_ATTN_COMBINE, stream, [&] { return launch_attn_combine(p, stream); });
     return err == hipSuccess ? SPEC_OK : SPEC_EHIP;
 }
 
@@ -261,7 +282,14 @@ spec_status spec_verify_attn(const spec_attn_args *attn, void *workspace, size_t
     const AttnPlan pl = plan_attn(attn);
     st = check_workspace(workspace, workspace_bytes, pl.total_bytes);
     if (st != SPEC_OK) return st;
-    return run_attn(attn, pl, static_cast<char *>(workspace), static_cast<hipStream_t>(hip_stream));
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const AttnParams ap = attn_params(attn, pl, static_cast<char *>(workspace));
+    if (!pl.use_mfma) return run_attn_generic(ap, attn->qkv_dtype, stream);
+    hipError_t err =
+        timed(SPEC_KERNEL_ATTN, stream, [&] { return launch_step_fused(&ap, pl.row_tiles, nullptr, stream); });
+    if (err == hipSuccess && !pl.fused_combine && pl.max_chunks > 1)
+        err = timed(SPEC_KERNEL_ATTN_COMBINE, stream, [&] { return launch_attn_combine(ap, stream); });
+    return err == hipSuccess ? SPEC_OK : SPEC_EHIP;
 }
 
 spec_status spec_reject_sample(const spec_reject_args *reject, void *workspace, size_t workspace_bytes,
@@ -272,7 +300,11 @@ spec_status spec_reject_sample(const spec_reject_args *reject, void *workspace, 
     const RejectPlan pl = plan_reject(reject, 0);
     st = check_workspace(workspace, workspace_bytes, pl.total_bytes);
     if (st != SPEC_OK) return st;
-    return run_reject(reject, pl, static_cast<char *>(workspace), static_cast<hipStream_t>(hip_stream));
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const RejectParams rp = reject_params(reject, pl, static_cast<char *>(workspace));
+    const hipError_t err =
+        timed(SPEC_KERNEL_REJECT, stream, [&] { return launch_step_fused(nullptr, 0, &rp, stream); });
+    return err == hipSuccess ? SPEC_OK : SPEC_EHIP;
 }
 
 spec_status spec_verify_step(const spec_attn_args *attn, const spec_reject_args *reject, void *workspace,
@@ -288,9 +320,21 @@ spec_status spec_verify_step(const spec_attn_args *attn, const spec_reject_args 
     st = check_workspace(workspace, workspace_bytes, apl.total_bytes + rpl.total_bytes);
     if (st != SPEC_OK) return st;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    st = run_attn(attn, apl, static_cast<char *>(workspace), stream);
+    const AttnParams ap = attn_params(attn, apl, static_cast<char *>(workspace));
+    const RejectParams rp = reject_params(reject, rpl, static_cast<char *>(workspace));
+    if (apl.use_mfma) {
+        // the whole step in one launch
+        hipError_t err =
+            timed(SPEC_KERNEL_STEP, stream, [&] { return launch_step_fused(&ap, apl.row_tiles, &rp, stream); });
+        if (err == hipSuccess && !apl.fused_combine && apl.max_chunks > 1)
+            err = timed(SPEC_KERNEL_ATTN_COMBINE, stream, [&] { return launch_attn_combine(ap, stream); });
+        return err == hipSuccess ? SPEC_OK : SPEC_EHIP;
+    }
+    st = run_attn_generic(ap, attn->qkv_dtype, stream);
     if (st != SPEC_OK) return st;
-    return run_reject(reject, rpl, static_cast<char *>(workspace), stream);
+    const hipError_t err =
+        timed(SPEC_KERNEL_REJECT, stream, [&] { return launch_step_fused(nullptr, 0, &rp, stream); });
+    return err == hipSuccess ? SPEC_OK : SPEC_EHIP;
 }
 
 spec_status spec_kv_repack_mfma(const void *src_k, const void *src_v, void *dst_k, void *dst_v, int32_t num_blocks,

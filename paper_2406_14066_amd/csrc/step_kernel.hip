@@ -1,0 +1,938 @@
+// The speculative-verification step as ONE kernel launch (arXiv 2406.14066:
+// "score" = lookahead attention of the k+1 query positions against the paged KV
+// cache, Section 2.2 / Section 4; "accept" = rejection sampling with bonus token,
+// Section 4; the accept rule is the cited speculative-sampling method's).
+//
+// The grid is a list of independent work items; a block's index selects its role:
+//
+//   [0, n_stat)            logit statistics: one (logit row, vocabulary segment)
+//                          each; the block that completes the LAST segment of a
+//                          request goes on to run that request's accept chain.
+//   [n_stat, n_stat+n_att) attention: one (request, KV head, KV chunk) each; the
+//                          block that completes the LAST chunk of a (request, KV
+//                          head) merges the chunk partials and writes the output.
+//   [.., +B*race_segs)     race for the next token: one (request, vocabulary
+//                          segment) each, which first recomputes the request's
+//                          (cheap) accept chain from the published statistics.
+//   [.., +B)               one final item per request: picks the race winner and
+//                          writes the request's outputs and counters.
+//
+// Attention blocks never wait: "last one out merges" is decided with one atomic
+// ticket per (request, KV head).  Race and final items consume what earlier items
+// of the grid published (tagged with the call's generation); by their place at
+// the end of the grid it is there when they are scheduled, and the bounded wait
+// that checks it can only end early, never hang: the producers precede the
+// consumers in dispatch order and wait for nothing.  (Same-address atomic tickets
+// cost about 0.3 us per arrival here, so they are kept for the attention chunks,
+// which arrive spread out in time, and avoided for the hundreds of statistics
+// blocks of a request, which arrive together.)  Tickets
+// carry the call's generation tag in their high half, so a workspace needs no
+// zero-initialisation and a call that never finished cannot poison the next;
+// the last arrival also resets its ticket, so a replayed HIP graph (same tag)
+// works too.  The rejection half is small and sits first in the grid: it runs
+// while the attention half streams the KV cache, and both are bound by HBM.
+//
+// Attention arithmetic, per 16-token page and 16-row tile (lane = 16*g + n):
+//   S^T[token][row] = K[token][:] . Q[row][:]        4 x v_mfma_f32_16x16x32_bf16
+//   base-2 online softmax on the lane's tokens 4g..4g+3 of query row n
+//   O^T[dim][row] += V^T[dim][token] . P^T[token][row]   8 x v_mfma_f32_16x16x16_bf16,
+//   P^T being S^T's own accumulator layout; P is fed as bf16 high + low parts so
+//   that its rounding does not limit the result.  All q_len * (Hq/Hkv) query rows
+//   sharing a KV head are fused into the N dimension: K and V are read once.
+//
+// Rejection arithmetic: the streaming part is fp32; what happens once per row or
+// per decision (segment sums, log-sum-exp, p/q of the draft token, the comparison
+// with u) is fp64.
+#include "common.h"
+
+#include <float.h>
+#include <math.h>
+
+namespace specv {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / kWave;
+constexpr int kD = 128;
+constexpr int kPageHeadBytes = SPEC_BLOCK_SIZE * kD * 2;  // 4096
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// ---------------------------------------------------------------------------
+// Tickets.  Word = generation << 32 | arrivals.  Returns how many blocks arrived
+// before this one.  The first arrival of a generation replaces whatever the word
+// held (garbage, or the leftovers of an older call).
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t ticket_arrive(unsigned long long *ticket, uint32_t generation)
+{
+    unsigned long long cur = __hip_atomic_load(ticket, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (;;) {
+        if ((uint32_t)(cur >> 32) == generation) return (uint32_t)atomicAdd(ticket, 1ull);
+        const unsigned long long first = ((unsigned long long)generation << 32) | 1ull;
+        const unsigned long long seen = atomicCAS(ticket, cur, first);
+        if (seen == cur) return 0u;
+        cur = seen;
+    }
+}
+
+__device__ __forceinline__ void ticket_reset(unsigned long long *ticket)
+{
+    __hip_atomic_store(ticket, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Data handed from one block to another inside the launch (chunk partials, row
+// statistics) is written and read with relaxed agent-scope atomic accesses, which
+// go past the non-coherent cache levels, and published by waiting for the
+// writes to complete before the ticket is taken.  A full agent-scope fence would
+// also write back and invalidate the whole L2 of the XCD on every block; that is
+// far too slow for thousands of blocks.
+__device__ __forceinline__ void publish_u64(unsigned long long *dst, unsigned long long v)
+{
+    __hip_atomic_store(dst, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ unsigned long long fetch_u64(const unsigned long long *src)
+{
+    return __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ unsigned long long pack_f32x2(float a, float b)
+{
+    return (unsigned long long)__float_as_uint(a) | ((unsigned long long)__float_as_uint(b) << 32);
+}
+
+__device__ __forceinline__ void writes_complete()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0);  // every outstanding store of this wavefront has been acknowledged
+}
+
+__device__ __forceinline__ void order_after_ticket()
+{
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
+
+// request that owns packed target row `row`: largest b with cu_q_len[b] <= row
+__device__ __forceinline__ int request_of_target_row(const int32_t *cu_q_len, int B, int row)
+{
+    int lo = 0, hi = B - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (cu_q_len[mid] <= row) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+// request that owns packed draft row `row`: largest b with cu_q_len[b] - b <= row
+__device__ __forceinline__ int request_of_draft_row(const int32_t *cu_q_len, int B, int row)
+{
+    int lo = 0, hi = B - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (cu_q_len[mid] - mid <= row) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+// ===========================================================================
+// Rejection half
+// ===========================================================================
+
+// Philox4x32-10 (Salmon et al., SC'11): ten rounds of two 32x32->64 multiplies,
+// a word permutation with key xor, and a Weyl sequence on the key.
+__device__ __forceinline__ uint4 philox4x32_10(uint4 c, uint32_t k0, uint32_t k1)
+{
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t hi_a = __umulhi(0xD2511F53u, c.x), lo_a = 0xD2511F53u * c.x;
+        const uint32_t hi_b = __umulhi(0xCD9E8D57u, c.z), lo_b = 0xCD9E8D57u * c.z;
+        c = make_uint4(hi_b ^ c.y ^ k0, lo_b, hi_a ^ c.w ^ k1, lo_a);
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    return c;
+}
+
+constexpr int kMaxStatSegments = 32;
+constexpr float kLog2eHi = 1.4426950216293335f;     // fp32(log2 e)
+constexpr float kLog2eLo = 1.9259629911266175e-8f;  // log2 e - kLog2eHi
+
+struct RejectShared {
+    float red_f[kWaves];
+    double red_d[kWaves];
+    double lse2[2 * SPEC_K_MAX + 1];  // log2-sum-exp: target rows 0..k, then draft rows 0..k-1
+    double u[SPEC_K_MAX], ratio[SPEC_K_MAX];
+    int accept[SPEC_K_MAX];
+    int m, near, last;
+    float best_score[kWaves];
+    int best_id[kWaves];
+    double seg_sum[2 * SPEC_K_MAX + 1][kMaxStatSegments];
+    float seg_off[2 * SPEC_K_MAX + 1][kMaxStatSegments];
+};
+
+// One (row, segment): offset and sum of 2^(x*log2e - offset) over the segment.
+// The running offset is integer-valued in base-2 units, so every rescale is an
+// exact power of two and x*log2(e) - offset is rounded once (log2 e enters as an
+// fp32 hi/lo pair inside fused multiply-adds).
+__device__ __forceinline__ void stats_block(const RejectParams &p, int row, int seg, RejectShared &sh)
+{
+    constexpr int UNROLL = 4;
+    const int tid = threadIdx.x;
+    const float *base = row < p.T ? p.target_logits + (size_t)row * p.V
+                                  : p.draft_logits + (size_t)(row - p.T) * p.V;
+    const int v0 = seg * p.stat_seg_len;
+    const int v1 = min(p.V, v0 + p.stat_seg_len);
+    const float4 *vec = reinterpret_cast<const float4 *>(base + v0);
+    const int nvec = (v1 - v0) >> 2;
+
+    float m = -FLT_MAX;   // largest logit seen
+    float off = kEmptyMax;
+    float s = 0.0f;
+    for (int i = tid; i < nvec; i += kThreads * UNROLL) {
+        float4 x[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const int idx = i + u * kThreads;
+            x[u] = idx < nvec ? vec[idx] : make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+        }
+        float cm = m;
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) cm = fmaxf(cm, fmaxf(fmaxf(x[u].x, x[u].y), fmaxf(x[u].z, x[u].w)));
+        if (cm > m) {
+            const float new_off = ceilf(cm * kLog2eHi);
+            s *= fast_exp2(off - new_off);
+            off = new_off;
+            m = cm;
+        }
+        const float noff = -off;
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            s += fast_exp2(fmaf(x[u].x, kLog2eHi, fmaf(x[u].x, kLog2eLo, noff)));
+            s += fast_exp2(fmaf(x[u].y, kLog2eHi, fmaf(x[u].y, kLog2eLo, noff)));
+            s += fast_exp2(fmaf(x[u].z, kLog2eHi, fmaf(x[u].z, kLog2eLo, noff)));
+            s += fast_exp2(fmaf(x[u].w, kLog2eHi, fmaf(x[u].w, kLog2eLo, noff)));
+        }
+    }
+
+    const int wave = tid / kWave, lane = tid % kWave;
+    float wm = off;
+#pragma unroll
+    for (int o = kWave / 2; o > 0; o >>= 1) wm = fmaxf(wm, __shfl_xor(wm, o));
+    if (lane == 0) sh.red_f[wave] = wm;
+    __syncthreads();
+    float boff = sh.red_f[0];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) boff = fmaxf(boff, sh.red_f[w]);
+    // one exact power-of-two rescale per thread, then the cross-thread sum in fp64
+    double sd = (double)s * (double)fast_exp2(off - boff);
+#pragma unroll
+    for (int o = kWave / 2; o > 0; o >>= 1) sd += __shfl_xor(sd, o);
+    if (lane == 0) sh.red_d[wave] = sd;
+    __syncthreads();
+    if (tid == 0) {
+        double total = 0.0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) total += sh.red_d[w];
+        // word 0: the sum; word 1: offset | generation tag, written once word 0 is in memory,
+        // so whoever sees this call's tag in word 1 may read word 0
+        unsigned long long *dst = reinterpret_cast<unsigned long long *>(p.stats + (size_t)row * p.stat_segments + seg);
+        publish_u64(dst + 0, (unsigned long long)__double_as_longlong(total));
+        writes_complete();
+        publish_u64(dst + 1, (unsigned long long)__float_as_uint(boff) | ((unsigned long long)p.generation << 32));
+    }
+}
+
+__device__ __forceinline__ float race_exponential(uint32_t word)
+{
+    // U' = n * 2^-24 with n = (word >> 8) + 1 in [1, 2^24]; e = -log(U').
+    const uint32_t n = (word >> 8) + 1u;
+    const uint32_t j = 16777216u - n;  // U' = 1 - j * 2^-24
+    if (j < 4096u) {
+        // -log(1 - x) = x + x^2/2 + x^3/3 + ..., x < 2^-12: three terms are exact to fp32
+        const float x = (float)j * 5.9604644775390625e-8f;
+        return x * fmaf(x, fmaf(x, 0.33333334f, 0.5f), 1.0f);
+    }
+    const float u = (float)n * 5.9604644775390625e-8f;
+    return -__builtin_amdgcn_logf(u) * kLn2;   // v_log_f32 is log2
+}
+
+// The race over vocabulary ids [v0, v1) of one request: best r_v / e_v, e_v = -log(U'_v).
+// draft_row == nullptr: weights are the target probabilities (bonus token);
+// otherwise the positive part of p - q.
+//   p_v = corr_t * 2^(x_v * log2e + off_t), off_t = fp32(-log2-sum-exp), corr_t the
+//   factor lost by rounding off_t.  Ties keep the lowest id; weights <= 0 never win.
+// Returns the block's best (score, id) to every thread.
+__device__ void race_segment(const RejectParams &p, const float *target_row, const float *draft_row, int b, int v0,
+                             int v1, float off_t, float corr_t, float off_d, float corr_d, RejectShared &sh,
+                             float &win_score, int &win_id)
+{
+    float best_score = -1.0f;
+    int best_id = 0x7FFFFFFF;
+    const int g_begin = v0 >> 2, g_end = v1 >> 2;
+    const uint32_t c3 = (p.step_hi24 << 8) | 1u;
+    constexpr int U = 2;  // row vectors in flight per thread
+    for (int g0 = g_begin + threadIdx.x; g0 < g_end; g0 += kThreads * U) {
+        float4 xt[U], xd[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int g = g0 + u * kThreads;
+            const float4 ninf = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+            xt[u] = g < g_end ? *reinterpret_cast<const float4 *>(target_row + 4 * g) : ninf;
+            xd[u] = (draft_row != nullptr && g < g_end) ? *reinterpret_cast<const float4 *>(draft_row + 4 * g) : ninf;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int g = g0 + u * kThreads;
+            if (g >= g_end) break;
+            const int v = 4 * g;
+            float r[4];
+            {
+                const float x[4] = {xt[u].x, xt[u].y, xt[u].z, xt[u].w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    r[e] = corr_t * fast_exp2(fmaf(x[e], kLog2eHi, fmaf(x[e], kLog2eLo, off_t)));
+            }
+            if (draft_row != nullptr) {
+                const float x[4] = {xd[u].x, xd[u].y, xd[u].z, xd[u].w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    r[e] -= corr_d * fast_exp2(fmaf(x[e], kLog2eHi, fmaf(x[e], kLog2eLo, off_d)));
+            }
+            const uint4 w = philox4x32_10(make_uint4((uint32_t)g, (uint32_t)b, p.step_lo, c3), p.seed_lo, p.seed_hi);
+            const uint32_t word[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (r[e] > 0.0f) {
+                    const float ex = race_exponential(word[e]);
+                    const float score = r[e] * __builtin_amdgcn_rcpf(ex);  // ex == 0 -> +inf
+                    if (score > best_score) {  // ids rise within a thread: strict > keeps the lowest
+                        best_score = score;
+                        best_id = v + e;
+                    }
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int o = kWave / 2; o > 0; o >>= 1) {
+        const float os = __shfl_xor(best_score, o);
+        const int oi = __shfl_xor(best_id, o);
+        if (os > best_score || (os == best_score && oi < best_id)) { best_score = os; best_id = oi; }
+    }
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    __syncthreads();
+    if (lane == 0) { sh.best_score[wave] = best_score; sh.best_id[wave] = best_id; }
+    __syncthreads();
+    win_score = sh.best_score[0];
+    win_id = sh.best_id[0];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) {
+        const float os = sh.best_score[w];
+        const int oi = sh.best_id[w];
+        if (os > win_score || (os == win_score && oi < win_id)) { win_score = os; win_id = oi; }
+    }
+    __syncthreads();
+}
+
+// Bounded wait until `ready` holds for every thread of the block (block-wide AND).
+// `probe` re-evaluates the condition; returns false if the limit ran out.
+template <typename F>
+__device__ __forceinline__ bool wait_all(int spin_limit, F probe)
+{
+    for (int spin = 0; spin < spin_limit; ++spin) {
+        if (__syncthreads_and(probe() ? 1 : 0)) return true;
+        __builtin_amdgcn_s_sleep(32);
+    }
+    return false;
+}
+
+// Accept chain of request b from the published row statistics.  Cheap (a few
+// hundred loads and fp64 operations), so every block that needs its result just
+// recomputes it.  Waits (bounded) until all of the request's statistics carry this
+// call's tag.  Leaves log2-sum-exp per row in sh.lse2, m in sh.m, the near-tie count
+// in sh.near.  Returns false if the statistics never arrived.
+__device__ bool accept_phase(const RejectParams &p, int b, RejectShared &sh, bool write_debug)
+{
+    const int tid = threadIdx.x;
+    const int row_t0 = p.cu_q_len[b];
+    const int k = p.cu_q_len[b + 1] - row_t0 - 1;
+    const int row_d0 = row_t0 - b;
+    const int nrows = 2 * k + 1;
+    const int nstat = nrows * p.stat_segments;
+
+    // the draft tokens' logits do not depend on the statistics: fetch them first
+    float tx = 0.0f, dx = 0.0f;
+    if (tid < k) {
+        const int x = p.draft_tokens[row_d0 + tid];
+        tx = p.target_logits[(size_t)(row_t0 + tid) * p.V + x];
+        dx = p.draft_logits[(size_t)(row_d0 + tid) * p.V + x];
+    }
+
+    auto stat_words = [&](int i) {
+        const int ri = i / p.stat_segments;
+        const int sg = i - ri * p.stat_segments;
+        const int row = ri <= k ? row_t0 + ri : p.T + row_d0 + (ri - k - 1);
+        return reinterpret_cast<const unsigned long long *>(p.stats + (size_t)row * p.stat_segments + sg);
+    };
+    const bool ok = wait_all(p.spin_limit, [&] {
+        bool mine = true;
+        for (int i = tid; i < nstat; i += kThreads)
+            mine = mine && ((uint32_t)(fetch_u64(stat_words(i) + 1) >> 32) == p.generation);
+        return mine;
+    });
+    if (!ok) return false;
+    order_after_ticket();
+    for (int i = tid; i < nstat; i += kThreads) {
+        const unsigned long long *st = stat_words(i);
+        const int ri = i / p.stat_segments;
+        const int sg = i - ri * p.stat_segments;
+        sh.seg_sum[ri][sg] = __longlong_as_double((long long)fetch_u64(st));
+        sh.seg_off[ri][sg] = __uint_as_float((uint32_t)fetch_u64(st + 1));
+    }
+    __syncthreads();
+    if (tid < nrows) {
+        float mx = kEmptyMax;
+        for (int sg = 0; sg < p.stat_segments; ++sg) mx = fmaxf(mx, sh.seg_off[tid][sg]);
+        double total = 0.0;
+        for (int sg = 0; sg < p.stat_segments; ++sg)
+            total += sh.seg_sum[tid][sg] * exp2((double)(sh.seg_off[tid][sg] - mx));   // exact power of two
+        sh.lse2[tid] = (double)mx + log2(total);
+    }
+    __syncthreads();
+
+    // accept tests, all evaluated in parallel; the chain is resolved below
+    if (tid < k) {
+        const double log2_p = (double)tx * kLog2eD - sh.lse2[tid];
+        const double log2_q = (double)dx * kLog2eD - sh.lse2[k + 1 + tid];
+        const double ratio = exp2(log2_p - log2_q);  // p = 0 -> 0, q = 0 < p -> inf, both 0 -> NaN (rejects)
+        const uint4 w = philox4x32_10(make_uint4((uint32_t)tid, (uint32_t)b, p.step_lo, (p.step_hi24 << 8) | 0u),
+                                      p.seed_lo, p.seed_hi);
+        const double u = (double)(w.x >> 8) * (1.0 / 16777216.0);
+        sh.u[tid] = u;
+        sh.ratio[tid] = ratio;
+        sh.accept[tid] = (u < ratio) ? 1 : 0;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int m = 0;
+        while (m < k && sh.accept[m]) ++m;
+        int near = 0;
+        const int evaluated = m + 1 < k ? m + 1 : k;
+        for (int i = 0; i < evaluated; ++i)
+            if (fabs(sh.u[i] - sh.ratio[i]) < 1e-6) ++near;
+        sh.m = m;
+        sh.near = near;
+    }
+    __syncthreads();
+    if (write_debug && p.debug_u_ratio != nullptr && tid < k) {
+        const bool evaluated = tid <= sh.m;
+        p.debug_u_ratio[2 * (size_t)(row_d0 + tid) + 0] = evaluated ? sh.u[tid] : (double)NAN;
+        p.debug_u_ratio[2 * (size_t)(row_d0 + tid) + 1] = evaluated ? sh.ratio[tid] : (double)NAN;
+    }
+    return true;
+}
+
+__device__ void stats_role(const RejectParams &p, int item, RejectShared &sh)
+{
+    const int row = item / p.stat_segments;
+    stats_block(p, row, item - row * p.stat_segments, sh);
+}
+
+// Offsets of the race rows of request b after accept_phase.
+struct RaceRows {
+    const float *trow, *drow;
+    float off_t, corr_t, off_d, corr_d;
+    int m, k, row_d0;
+};
+
+__device__ __forceinline__ RaceRows race_rows(const RejectParams &p, int b, const RejectShared &sh)
+{
+    RaceRows rr;
+    const int row_t0 = p.cu_q_len[b];
+    rr.k = p.cu_q_len[b + 1] - row_t0 - 1;
+    rr.row_d0 = row_t0 - b;
+    rr.m = sh.m;
+    const double off_t_exact = -sh.lse2[rr.m];
+    rr.off_t = (float)off_t_exact;
+    rr.corr_t = (float)exp2(off_t_exact - (double)rr.off_t);
+    rr.off_d = 0.0f;
+    rr.corr_d = 0.0f;
+    rr.trow = p.target_logits + (size_t)(row_t0 + rr.m) * p.V;
+    rr.drow = nullptr;
+    if (rr.m < rr.k) {
+        const double off_d_exact = -sh.lse2[rr.k + 1 + rr.m];
+        rr.off_d = (float)off_d_exact;
+        rr.corr_d = (float)exp2(off_d_exact - (double)rr.off_d);
+        rr.drow = p.draft_logits + (size_t)(rr.row_d0 + rr.m) * p.V;
+    }
+    return rr;
+}
+
+// One (request, vocabulary segment) of the race.  Race items come after every
+// statistics item and every attention item in the grid, so when one is scheduled
+// its request's statistics have normally long been published; the bounded wait in
+// accept_phase only matters for launches with little else to do.  The statistics
+// blocks it waits for never wait themselves and precede it in dispatch order, so
+// the wait ends; should it ever run out, the request's outputs are set to -1.
+__device__ void race_role(const RejectParams &p, int item, RejectShared &sh)
+{
+    const int tid = threadIdx.x;
+    const int b = item / p.race_segments;
+    const int seg = item - b * p.race_segments;
+    if (!accept_phase(p, b, sh, seg == 0)) {
+        if (tid == 0 && seg == 0) { p.accepted_len[b] = -1; p.next_token[b] = -1; }
+        return;
+    }
+    const RaceRows rr = race_rows(p, b, sh);
+    const int v0 = seg * p.race_seg_len;
+    const int v1 = min(p.V, v0 + p.race_seg_len);
+    float win_score;
+    int win_id;
+    race_segment(p, rr.trow, rr.drow, b, v0, v1, rr.off_t, rr.corr_t, rr.off_d, rr.corr_d, sh, win_score, win_id);
+    if (tid == 0) {
+        unsigned long long *dst = p.race_partial + 2 * ((size_t)b * p.race_segments + seg);
+        publish_u64(dst + 0, ((unsigned long long)__float_as_uint(win_score) << 32) | (unsigned long long)(uint32_t)win_id);
+        writes_complete();
+        publish_u64(dst + 1, (unsigned long long)p.generation << 32);
+    }
+}
+
+// Last stage of request b (one item per request at the very end of the grid):
+// waits (bounded) for the request's race segments, picks the winner, writes the
+// outputs and counters, and clears the request's tags so that a replay of the
+// same launch (HIP graph) starts clean.
+__device__ void final_role(const RejectParams &p, int b, RejectShared &sh)
+{
+    const int tid = threadIdx.x;
+    unsigned long long *part = p.race_partial + 2 * (size_t)b * p.race_segments;
+    const bool ok = wait_all(p.spin_limit, [&] {
+        return tid >= p.race_segments || (uint32_t)(fetch_u64(part + 2 * tid + 1) >> 32) == p.generation;
+    });
+    if (!ok || !accept_phase(p, b, sh, false)) {
+        if (tid == 0) { p.accepted_len[b] = -1; p.next_token[b] = -1; }
+        return;
+    }
+    order_after_ticket();
+    const RaceRows rr = race_rows(p, b, sh);
+
+    float best_score = -1.0f;
+    int best_id = 0x7FFFFFFF;
+    if (tid < p.race_segments) {   // race_segments <= 64: wavefront 0 holds them all
+        const unsigned long long v = fetch_u64(part + 2 * tid);
+        best_score = __uint_as_float((uint32_t)(v >> 32));
+        best_id = (int)(uint32_t)v;
+    }
+#pragma unroll
+    for (int o = kWave / 2; o > 0; o >>= 1) {
+        const float os = __shfl_xor(best_score, o);
+        const int oi = __shfl_xor(best_id, o);
+        if (os > best_score || (os == best_score && oi < best_id)) { best_score = os; best_id = oi; }
+    }
+    if (tid == 0) { sh.best_score[0] = best_score; sh.best_id[0] = best_id; }
+    __syncthreads();
+    float win_score = sh.best_score[0];
+    int win_id = sh.best_id[0];
+    __syncthreads();
+    if (!(win_score > 0.0f)) {
+        // p - q has no positive entry (p == q to rounding): draw from p instead
+        race_segment(p, rr.trow, nullptr, b, 0, p.V, rr.off_t, rr.corr_t, 0.0f, 0.0f, sh, win_score, win_id);
+    }
+    const int m = rr.m, k = rr.k;
+    if (tid == 0) {
+        p.accepted_len[b] = m;
+        p.next_token[b] = win_id;
+        if (p.out_tokens != nullptr) {
+            int32_t *row = p.out_tokens + (size_t)b * (SPEC_K_MAX + 1);
+            for (int i = 0; i <= SPEC_K_MAX; ++i)
+                row[i] = i < m ? p.draft_tokens[rr.row_d0 + i] : (i == m ? win_id : -1);
+        }
+        atomicAdd(&p.counters[0], (unsigned long long)k);
+        atomicAdd(&p.counters[1], (unsigned long long)m);
+        atomicAdd(&p.counters[2], (unsigned long long)(m + 1 < k ? m + 1 : k));
+        atomicAdd(&p.counters[3], (unsigned long long)(m + 1));
+        atomicAdd(&p.counters[4], (unsigned long long)sh.near);
+        atomicAdd(&p.counters[5], 1ull);
+    }
+    // clear this request's tags
+    const int row_t0 = p.cu_q_len[b];
+    const int nstat = (2 * k + 1) * p.stat_segments;
+    for (int i = tid; i < nstat; i += kThreads) {
+        const int ri = i / p.stat_segments;
+        const int sg = i - ri * p.stat_segments;
+        const int row = ri <= k ? row_t0 + ri : p.T + rr.row_d0 + (ri - k - 1);
+        publish_u64(reinterpret_cast<unsigned long long *>(p.stats + (size_t)row * p.stat_segments + sg) + 1, 0ull);
+    }
+    if (tid < p.race_segments) publish_u64(part + 2 * tid + 1, 0ull);
+}
+
+// ===========================================================================
+// Attention half
+// ===========================================================================
+struct PageRegs {
+    u32x4 k[4];  // k[kk]: token n, dims 32*kk + 8g .. +7
+    u32x4 v[4];  // v[pp]: dims 32*pp + n (low half) and 32*pp + 16 + n (high half), tokens 4g .. 4g+3
+};
+
+template <int NT>
+struct AttnShared {
+    f32x4 acc[2][NT][8][kWave];
+    float m[2][NT][kWave];
+    float l[2][NT][kWave];
+    int last;
+};
+
+template <int NT, bool SPLIT_P>
+__device__ void attn_role(const AttnParams &p, int item, AttnShared<NT> &sh)
+{
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63;
+    const int n16 = lane & 15;
+    const int g = lane >> 4;
+    const int chunk = item % p.max_chunks;
+    const int unit = item / p.max_chunks;
+    const int kvh = unit % p.Hkv;
+    const int b = unit / p.Hkv;
+
+    const int L = p.kv_len[b];
+    const int nchunks = (L + p.chunk_tokens - 1) / p.chunk_tokens;
+    if (chunk >= nchunks) return;
+    // even chunks per request, page aligned (never longer than chunk_tokens)
+    const int C = ((L + nchunks - 1) / nchunks + SPEC_BLOCK_SIZE - 1) & ~(SPEC_BLOCK_SIZE - 1);
+    const int row0 = p.cu_q_len[b];
+    const int q_len = p.cu_q_len[b + 1] - row0;
+    const int group = p.Hq / p.Hkv;
+    const int rows = q_len * group;
+    const int tok0 = chunk * C;
+    const int tok1 = min(L, tok0 + C);
+    const int npages = (tok1 - tok0 + SPEC_BLOCK_SIZE - 1) / SPEC_BLOCK_SIZE;  // <= 256
+    const int page0 = tok0 / SPEC_BLOCK_SIZE;
+
+    // block-table entries of this wavefront's pages (wave, wave+4, ...), one per lane
+    int bt = 0;
+    if (wave + kWaves * lane < npages)
+        bt = p.block_table[(size_t)b * p.max_blocks_per_req + page0 + wave + kWaves * lane];
+
+    // Q as the B operand of S^T = K Q^T, and each lane's last visible key
+    bf16x8 qreg[NT][4];
+    int limit[NT];
+    int out_row[NT];   // packed (token row * Hq + head) of this lane's query row, -1 if padding
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int r = nt * 16 + n16;
+        const bool valid = r < rows;
+        const int j = valid ? r / group : 0;
+        const int gq = valid ? r % group : 0;
+        const size_t rh = (size_t)(row0 + j) * p.Hq + kvh * group + gq;
+        const __bf16 *qp = static_cast<const __bf16 *>(p.q) + rh * kD + g * 8;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+            qreg[nt][kk] = valid ? *reinterpret_cast<const bf16x8 *>(qp + kk * 32) : z;
+        }
+        limit[nt] = valid ? L - q_len + j : -1;
+        out_row[nt] = valid ? (int)rh : -1;
+    }
+
+    const char *kbase = static_cast<const char *>(p.k_cache) + (size_t)kvh * kPageHeadBytes + lane * 16;
+    const char *vbase = static_cast<const char *>(p.v_cache) + (size_t)kvh * kPageHeadBytes + lane * 16;
+    const size_t page_stride = (size_t)p.Hkv * kPageHeadBytes;
+
+    auto load_page = [&](int pi, PageRegs &r) {
+        if (pi < npages) {
+            const int page = __builtin_amdgcn_readlane(bt, pi >> 2);   // pi = wave + 4 * (lane index)
+            const char *kp = kbase + (size_t)page * page_stride;
+            const char *vp = vbase + (size_t)page * page_stride;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) r.k[i] = *reinterpret_cast<const u32x4 *>(kp + i * 1024);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) r.v[i] = *reinterpret_cast<const u32x4 *>(vp + i * 1024);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                r.k[i] = (u32x4){0, 0, 0, 0};
+                r.v[i] = (u32x4){0, 0, 0, 0};
+            }
+        }
+    };
+
+    f32x4 acc[NT][8];
+    float m_run[NT], l_run[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        m_run[nt] = kEmptyMax;
+        l_run[nt] = 0.0f;
+#pragma unroll
+        for (int mt = 0; mt < 8; ++mt) acc[nt][mt] = (f32x4){0.0f, 0.0f, 0.0f, 0.0f};
+    }
+
+    const int first_masked_token = L - q_len + 1;  // keys from here on are hidden from some row (or past the end)
+
+    PageRegs cur;
+    load_page(wave, cur);
+    for (int pi = wave; pi < npages; pi += kWaves) {
+        PageRegs nxt;
+        load_page(pi + kWaves, nxt);
+
+        const int page_tok = tok0 + pi * SPEC_BLOCK_SIZE;
+        const bool need_mask = page_tok + SPEC_BLOCK_SIZE > first_masked_token;
+        const int tbase = page_tok + 4 * g;
+
+        if (page_tok + SPEC_BLOCK_SIZE > L) {
+            // last page of the request: slots past kv_len may hold anything; clear their V
+            const int nvalid = min(max(L - tbase, 0), 4);
+            const uint32_t lo = nvalid >= 2 ? 0xFFFFFFFFu : (nvalid == 1 ? 0x0000FFFFu : 0u);
+            const uint32_t hi = nvalid >= 4 ? 0xFFFFFFFFu : (nvalid == 3 ? 0x0000FFFFu : 0u);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                cur.v[i].x &= lo; cur.v[i].y &= hi;
+                cur.v[i].z &= lo; cur.v[i].w &= hi;
+            }
+        }
+
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            f32x4 s = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+                s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, cur.k[kk]), qreg[nt][kk], s, 0, 0, 0);
+            s *= p.scale_log2;
+            if (need_mask) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (tbase + r > limit[nt]) s[r] = -INFINITY;
+            }
+            float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
+            mx = fmaxf(mx, __shfl_xor(mx, 16));
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float m_new = fmaxf(m_run[nt], mx);
+            const float alpha = fast_exp2(m_run[nt] - m_new);
+            f32x4 pr;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) pr[r] = fast_exp2(s[r] - m_new);
+            l_run[nt] = l_run[nt] * alpha + ((pr[0] + pr[1]) + (pr[2] + pr[3]));
+            m_run[nt] = m_new;
+            if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+                for (int mt = 0; mt < 8; ++mt) acc[nt][mt] *= alpha;
+            }
+            const bf16x4 p_hi = __builtin_convertvector(pr, bf16x4);
+            bf16x4 p_lo;
+            if (SPLIT_P) p_lo = __builtin_convertvector(pr - __builtin_convertvector(p_hi, f32x4), bf16x4);
+#pragma unroll
+            for (int mt = 0; mt < 8; ++mt) {
+                const u32x4 vv = cur.v[mt >> 1];
+                const u32x2 half = (mt & 1) ? (u32x2){vv.z, vv.w} : (u32x2){vv.x, vv.y};
+                const bf16x4 va = __builtin_bit_cast(bf16x4, half);
+                acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va, p_hi, acc[nt][mt], 0, 0, 0);
+                if (SPLIT_P) acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va, p_lo, acc[nt][mt], 0, 0, 0);
+            }
+        }
+        cur = nxt;
+    }
+
+    // each lane summed its own four tokens per page: finish the row sums
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        l_run[nt] += __shfl_xor(l_run[nt], 16);
+        l_run[nt] += __shfl_xor(l_run[nt], 32);
+    }
+
+    // merge the four wavefronts: 2,3 -> 0,1 then 1 -> 0
+    auto put = [&](int buf) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+#pragma unroll
+            for (int mt = 0; mt < 8; ++mt) sh.acc[buf][nt][mt][lane] = acc[nt][mt];
+            sh.m[buf][nt][lane] = m_run[nt];
+            sh.l[buf][nt][lane] = l_run[nt];
+        }
+    };
+    auto merge = [&](int buf) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const float mo = sh.m[buf][nt][lane];
+            const float lo = sh.l[buf][nt][lane];
+            const float mn = fmaxf(m_run[nt], mo);
+            const float wa = fast_exp2(m_run[nt] - mn);
+            const float wb = fast_exp2(mo - mn);
+            l_run[nt] = l_run[nt] * wa + lo * wb;
+            m_run[nt] = mn;
+#pragma unroll
+            for (int mt = 0; mt < 8; ++mt) acc[nt][mt] = acc[nt][mt] * wa + sh.acc[buf][nt][mt][lane] * wb;
+        }
+    };
+    if (wave >= 2) put(wave - 2);
+    __syncthreads();
+    if (wave < 2) merge(wave);
+    __syncthreads();
+    if (wave == 1) put(0);
+    __syncthreads();
+
+    if (nchunks == 1) {
+        // the only chunk of this (request, KV head): normalise and write the output
+        if (wave != 0) return;
+        merge(0);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            if (out_row[nt] < 0) continue;
+            const float inv = 1.0f / l_run[nt];
+            float *dst = p.out + (size_t)out_row[nt] * kD + 4 * g;
+#pragma unroll
+            for (int mt = 0; mt < 8; ++mt) *reinterpret_cast<f32x4 *>(dst + 16 * mt) = acc[nt][mt] * inv;
+        }
+        return;
+    }
+
+    if (wave == 0) {
+        merge(0);
+        // one partial per query row: acc[dim], running max, running sum
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            if (out_row[nt] < 0) continue;
+            const size_t slot = (size_t)out_row[nt] * p.max_chunks + chunk;
+            unsigned long long *dst = reinterpret_cast<unsigned long long *>(p.ws_acc + slot * kD + 4 * g);
+#pragma unroll
+            for (int mt = 0; mt < 8; ++mt) {
+                publish_u64(dst + 8 * mt + 0, pack_f32x2(acc[nt][mt][0], acc[nt][mt][1]));
+                publish_u64(dst + 8 * mt + 1, pack_f32x2(acc[nt][mt][2], acc[nt][mt][3]));
+            }
+            if (g == 0)
+                publish_u64(reinterpret_cast<unsigned long long *>(p.ws_ml + slot * 2), pack_f32x2(m_run[nt], l_run[nt]));
+        }
+        if (!p.fused_combine) return;   // a separate combine launch merges the partials
+        writes_complete();  // the partial is in memory before the ticket is taken
+        if (lane == 0) {
+            unsigned long long *ticket = &p.tickets[unit];
+            const uint32_t before = ticket_arrive(ticket, p.generation);
+            const int last = (before + 1u == (uint32_t)nchunks) ? 1 : 0;
+            if (last) ticket_reset(ticket);
+            sh.last = last;
+        }
+    }
+    if (!p.fused_combine) return;
+    __syncthreads();
+    if (!sh.last) return;
+    order_after_ticket();
+
+    // Last chunk of this (request, KV head) to finish: merge all chunks in chunk order.
+    // Half a wavefront takes a query row (four head dims per lane); every load of a
+    // pass is issued before the first is used, so a pass costs one memory round trip.
+    constexpr int MAXC = 16;   // the plan guarantees nchunks <= MAXC on this path
+    const int half = lane >> 5, l32 = lane & 31;
+    for (int r0 = 2 * wave; r0 < rows; r0 += 2 * kWaves) {
+        const int r = r0 + half;
+        const bool rv = r < rows;
+        const int rr = rv ? r : 0;
+        const size_t rh = (size_t)(row0 + rr / group) * p.Hq + kvh * group + rr % group;
+        const size_t base = rh * p.max_chunks;
+        const unsigned long long *ml = reinterpret_cast<const unsigned long long *>(p.ws_ml) + base;
+        const unsigned long long *pa =
+            reinterpret_cast<const unsigned long long *>(p.ws_acc) + base * (kD / 2) + 2 * l32;
+        unsigned long long mlv[MAXC], a0[MAXC], a1[MAXC];
+#pragma unroll
+        for (int c = 0; c < MAXC; ++c) {
+            const bool on = rv && c < nchunks;
+            mlv[c] = on ? fetch_u64(ml + c) : pack_f32x2(kEmptyMax, 0.0f);
+            a0[c] = on ? fetch_u64(pa + (size_t)c * (kD / 2)) : 0ull;
+            a1[c] = on ? fetch_u64(pa + (size_t)c * (kD / 2) + 1) : 0ull;
+        }
+        float mx = kEmptyMax;
+#pragma unroll
+        for (int c = 0; c < MAXC; ++c) mx = fmaxf(mx, __uint_as_float((uint32_t)mlv[c]));
+        float denom = 0.0f;
+        f32x4 o = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int c = 0; c < MAXC; ++c) {
+            const float w = fast_exp2(__uint_as_float((uint32_t)mlv[c]) - mx);
+            denom = fmaf(w, __uint_as_float((uint32_t)(mlv[c] >> 32)), denom);
+            o[0] = fmaf(w, __uint_as_float((uint32_t)a0[c]), o[0]);
+            o[1] = fmaf(w, __uint_as_float((uint32_t)(a0[c] >> 32)), o[1]);
+            o[2] = fmaf(w, __uint_as_float((uint32_t)a1[c]), o[2]);
+            o[3] = fmaf(w, __uint_as_float((uint32_t)(a1[c] >> 32)), o[3]);
+        }
+        if (rv) *reinterpret_cast<f32x4 *>(p.out + rh * kD + 4 * l32) = o * (1.0f / denom);
+    }
+}
+
+// ===========================================================================
+// The kernel
+// ===========================================================================
+template <int NT, bool HAS_ATTN, bool HAS_REJECT>
+__global__ __launch_bounds__(kThreads, 2) void spec_step_kernel(AttnParams ap, RejectParams rp, int n_stat_items,
+                                                                 int n_attn_items)
+{
+    const int item = blockIdx.x;
+    if constexpr (HAS_REJECT) {
+        __shared__ RejectShared rsh;
+        if (item < n_stat_items) {
+            stats_role(rp, item, rsh);
+            return;
+        }
+        const int after = item - n_stat_items - n_attn_items;
+        if (after >= 0) {
+            const int n_race = rp.B * rp.race_segments;
+            if (after < n_race) race_role(rp, after, rsh);
+            else final_role(rp, after - n_race, rsh);
+            return;
+        }
+    }
+    if constexpr (HAS_ATTN) {
+        __shared__ AttnShared<NT> ash;
+        attn_role<NT, true>(ap, item - n_stat_items, ash);
+    }
+}
+
+template <int NT, bool HAS_ATTN, bool HAS_REJECT>
+hipError_t launch(const AttnParams &ap, const RejectParams &rp, int n_stat, int n_attn, int n_race, hipStream_t stream)
+{
+    hipLaunchKernelGGL((spec_step_kernel<NT, HAS_ATTN, HAS_REJECT>), dim3(n_stat + n_attn + n_race), dim3(kThreads), 0,
+                       stream, ap, rp, n_stat, n_attn);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_step_fused(const AttnParams *attn, int row_tiles, const RejectParams *reject, hipStream_t stream)
+{
+    AttnParams ap = {};
+    RejectParams rp = {};
+    int n_stat = 0, n_attn = 0, n_race = 0;
+    if (reject != nullptr) {
+        rp = *reject;
+        if (rp.stat_segments > kMaxStatSegments || rp.race_segments > kWave || rp.spin_limit < 1)
+            return hipErrorInvalidValue;
+        n_stat = (2 * rp.T - rp.B) * rp.stat_segments;
+        n_race = rp.B * rp.race_segments + rp.B;   // race segments, then one final item per request
+    }
+    if (attn != nullptr) {
+        ap = *attn;
+        if (ap.d != kD || ap.chunk_tokens > 4096 || ap.chunk_tokens % SPEC_BLOCK_SIZE != 0 || row_tiles < 1 ||
+            row_tiles > 3 || (ap.fused_combine && ap.max_chunks > 16))
+            return hipErrorInvalidValue;
+        n_attn = ap.B * ap.Hkv * ap.max_chunks;
+    }
+    if (attn == nullptr) return launch<1, false, true>(ap, rp, n_stat, 0, n_race, stream);
+    if (reject == nullptr) {
+        switch (row_tiles) {
+            case 1: return launch<1, true, false>(ap, rp, 0, n_attn, 0, stream);
+            case 2: return launch<2, true, false>(ap, rp, 0, n_attn, 0, stream);
+            default: return launch<3, true, false>(ap, rp, 0, n_attn, 0, stream);
+        }
+    }
+    switch (row_tiles) {
+        case 1: return launch<1, true, true>(ap, rp, n_stat, n_attn, n_race, stream);
+        case 2: return launch<2, true, true>(ap, rp, n_stat, n_attn, n_race, stream);
+        default: return launch<3, true, true>(ap, rp, n_stat, n_attn, n_race, stream);
+    }
+}
+
+}  // namespace specv

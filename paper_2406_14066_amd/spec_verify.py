@@ -56,8 +56,8 @@ EXPORTS = (
     "spec_validate_attn", "spec_validate_reject", "spec_kv_repack_mfma", "spec_status_string",
     "spec_verify_version", "spec_profile_begin", "spec_profile_end",
 )
-NUM_KERNELS = 4
-KERNEL_NAMES = ("attn_partial", "attn_combine", "logit_stats", "accept_race")
+NUM_KERNELS = 5
+KERNEL_NAMES = ("step", "attn", "attn_generic", "attn_combine", "reject")
 
 _lib = None
 
