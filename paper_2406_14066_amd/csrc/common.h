@@ -51,21 +51,24 @@ struct AttnParams {
     unsigned long long *tickets;
     uint32_t generation;  // tags this call's ticket values, never 0
     int32_t fused_combine;        // matrix kernel: the last chunk's block merges the partials (needs max_chunks <= 16)
+    int32_t split_p;              // feed the softmax weights to the PV product as bf16 high + low parts
     int32_t single_chunk_direct;  // requests with one chunk were written straight to `out`: the combine kernel skips them
 };
 
 // ---------------------------------------------------------------- rejection
-struct RowStat {   // one vocabulary segment of one logit row
-    double sum;    // sum_v 2^(x_v * log2(e) - off2)
-    float off2;    // integer-valued base-2 offset, about max_v x_v * log2(e)
-    uint32_t tag;  // generation of the call that wrote it, 0 = empty
-};
+// Records handed between the rejection stages are arrays of 8-byte words, each a
+// 32-bit payload with the call's generation tag in the high half:
+//   statistics of one (row, vocabulary segment): 3 words: low and high half of
+//     sum_v 2^(x_v*log2(e) - off2) as fp64, and off2 (integer-valued base-2 offset) as fp32
+//   race partial of one (request, segment): 2 words: best score (fp32), its id
+//   race info of one request: m | k << 8 | near ties << 16
+constexpr int kStatWords = 3;
 
 struct RejectPlan {
     int32_t stat_segments, stat_seg_len;   // vocabulary segments per row in the statistics pass
     int32_t race_segments, race_seg_len;   // vocabulary segments per request in the race
-    size_t stats_off, stats_bytes;         // RowStat [rows][stat_segments]
-    size_t partial_off, partial_bytes;     // race partials [B][race_segments][2]
+    size_t stats_off, stats_bytes;         // [rows][stat_segments][3] words
+    size_t partial_off, partial_bytes;     // race partials [B][race_segments][2], then race info [B]
     size_t total_bytes;
 };
 
@@ -80,8 +83,9 @@ struct RejectParams {
     int32_t stat_segments, stat_seg_len;
     int32_t race_segments, race_seg_len;
     int32_t spin_limit;                  // polls a race block spends waiting for its request's accept phase
-    RowStat *stats;                      // [rows][stat_segments]; `tag` holds the generation once valid
-    unsigned long long *race_partial;    // [B][race_segments][2]: best (score, id) of a segment; generation tag
+    unsigned long long *stats;           // [rows][stat_segments][3]
+    unsigned long long *race_partial;    // [B][race_segments][2]
+    unsigned long long *race_info;       // [B]
     uint32_t generation;
 };
 

@@ -152,9 +152,9 @@ RejectPlan plan_reject(const spec_reject_args *r, size_t base)
     RejectPlan pl;
     memset(&pl, 0, sizeof pl);
     const int rows = 2 * r->T - r->B;
-    // statistics: about 512 blocks in all, segments of >= 4096 logits, at most 32 per row
-    int segs = (512 + rows - 1) / rows;
-    const int max_by_len = (r->V + 4095) / 4096;
+    // statistics: about 256 blocks in all, segments of >= 8192 logits, at most 32 per row
+    int segs = (256 + rows - 1) / rows;
+    const int max_by_len = (r->V + 8191) / 8192;
     if (segs > max_by_len) segs = max_by_len;
     if (segs > 32) segs = 32;
     if (segs < 1) segs = 1;
@@ -162,9 +162,9 @@ RejectPlan plan_reject(const spec_reject_args *r, size_t base)
     seg_len = (seg_len + 3) / 4 * 4;
     pl.stat_seg_len = seg_len;
     pl.stat_segments = (r->V + seg_len - 1) / seg_len;
-    // race: about 1024 blocks in all, segments of >= 1024 vocabulary ids, at most 64 per request
-    int rsegs = (1024 + r->B - 1) / r->B;
-    const int rmax_by_len = (r->V + 1023) / 1024;
+    // race: about 512 blocks in all, segments of >= 2048 vocabulary ids, at most 64 per request
+    int rsegs = (512 + r->B - 1) / r->B;
+    const int rmax_by_len = (r->V + 2047) / 2048;
     if (rsegs > rmax_by_len) rsegs = rmax_by_len;
     if (rsegs > 64) rsegs = 64;
     if (rsegs < 1) rsegs = 1;
@@ -174,9 +174,9 @@ RejectPlan plan_reject(const spec_reject_args *r, size_t base)
     pl.race_segments = (r->V + rlen - 1) / rlen;
 
     pl.stats_off = base;
-    pl.stats_bytes = align_up((size_t)rows * pl.stat_segments * sizeof(RowStat));
+    pl.stats_bytes = align_up((size_t)rows * pl.stat_segments * kStatWords * sizeof(unsigned long long));
     pl.partial_off = pl.stats_off + pl.stats_bytes;
-    pl.partial_bytes = align_up((size_t)r->B * pl.race_segments * 2 * sizeof(unsigned long long));
+    pl.partial_bytes = align_up(((size_t)r->B * pl.race_segments * 2 + r->B) * sizeof(unsigned long long));
     pl.total_bytes = pl.stats_bytes + pl.partial_bytes;
     return pl;
 }
@@ -215,6 +215,8 @@ AttnParams attn_params(const spec_attn_args *a, const AttnPlan &pl, char *ws)
     p.generation = next_generation();
     p.fused_combine = pl.fused_combine;
     p.single_chunk_direct = pl.use_mfma;
+    p.split_p = 1;
+    if (const char *e = getenv("SPEC_VERIFY_SPLIT_P")) p.split_p = (e[0] != '0');   // experiment switch
     return p;
 }
 
@@ -235,8 +237,9 @@ RejectParams reject_params(const spec_reject_args *r, const RejectPlan &pl, char
     p.stat_segments = pl.stat_segments; p.stat_seg_len = pl.stat_seg_len;
     p.race_segments = pl.race_segments; p.race_seg_len = pl.race_seg_len;
     p.spin_limit = 1 << 20;   // about a second of polling; never reached in a healthy launch
-    p.stats = reinterpret_cast<RowStat *>(ws + pl.stats_off);
+    p.stats = reinterpret_cast<unsigned long long *>(ws + pl.stats_off);
     p.race_partial = reinterpret_cast<unsigned long long *>(ws + pl.partial_off);
+    p.race_info = p.race_partial + (size_t)r->B * pl.race_segments * 2;
     p.generation = next_generation();
     return p;
 }

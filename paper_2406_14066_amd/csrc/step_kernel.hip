@@ -3,26 +3,28 @@
 // cache, Section 2.2 / Section 4; "accept" = rejection sampling with bonus token,
 // Section 4; the accept rule is the cited speculative-sampling method's).
 //
-// The grid is a list of independent work items; a block's index selects its role:
+// The grid is a list of work items; a block's index selects its role:
 //
-//   [0, n_stat)            logit statistics: one (logit row, vocabulary segment)
-//                          each; the block that completes the LAST segment of a
-//                          request goes on to run that request's accept chain.
-//   [n_stat, n_stat+n_att) attention: one (request, KV head, KV chunk) each; the
-//                          block that completes the LAST chunk of a (request, KV
-//                          head) merges the chunk partials and writes the output.
-//   [.., +B*race_segs)     race for the next token: one (request, vocabulary
-//                          segment) each, which first recomputes the request's
-//                          (cheap) accept chain from the published statistics.
-//   [.., +B)               one final item per request: picks the race winner and
-//                          writes the request's outputs and counters.
+//   statistics   one (logit row, vocabulary segment) each: offset and sum of
+//                exponentials, published with the call's generation tag.
+//   race         one (request, vocabulary segment) each: recomputes the request's
+//                (cheap) accept chain from the published statistics, then races
+//                its segment for the next token.
+//   final        one per request: picks the race winner, writes the request's
+//                outputs and counters.
+//   attention    one (request, KV head, KV chunk) each; the block that completes
+//                the LAST chunk of a (request, KV head) merges the chunk partials
+//                and writes the output.
+// The rejection items keep that order among themselves and are spread evenly among
+// the attention items (see GridSplit), so that the rejection half, whose stages
+// depend on each other, runs underneath the long attention stream.
 //
 // Attention blocks never wait: "last one out merges" is decided with one atomic
 // ticket per (request, KV head).  Race and final items consume what earlier items
 // of the grid published (tagged with the call's generation); by their place at
-// the end of the grid it is there when they are scheduled, and the bounded wait
-// that checks it can only end early, never hang: the producers precede the
-// consumers in dispatch order and wait for nothing.  (Same-address atomic tickets
+// later in the grid the producers were scheduled before them, and the bounded wait
+// that checks for the data can only end early, never hang: the producers precede
+// the consumers in dispatch order and wait for nothing.  (Same-address atomic tickets
 // cost about 0.3 us per arrival here, so they are kept for the attention chunks,
 // which arrive spread out in time, and avoided for the hundreds of statistics
 // blocks of a request, which arrive together.)  Tickets
@@ -56,6 +58,7 @@ constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
 constexpr int kD = 128;
 constexpr int kPageHeadBytes = SPEC_BLOCK_SIZE * kD * 2;  // 4096
+constexpr int kBufferFlags = 0x00020000;   // raw 32-bit buffer descriptor, word 3
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
@@ -107,6 +110,19 @@ __device__ __forceinline__ unsigned long long fetch_u64(const unsigned long long
 __device__ __forceinline__ unsigned long long pack_f32x2(float a, float b)
 {
     return (unsigned long long)__float_as_uint(a) | ((unsigned long long)__float_as_uint(b) << 32);
+}
+
+// A 32-bit payload and the call's generation tag in one 8-byte word: written and read
+// atomically, so a reader that finds this call's tag also has the payload, with no
+// ordering needed between the words of a record.
+__device__ __forceinline__ void publish_tagged(unsigned long long *dst, uint32_t payload, uint32_t generation)
+{
+    publish_u64(dst, (unsigned long long)payload | ((unsigned long long)generation << 32));
+}
+
+__device__ __forceinline__ bool tagged_ok(unsigned long long word, uint32_t generation)
+{
+    return (uint32_t)(word >> 32) == generation;
 }
 
 __device__ __forceinline__ void writes_complete()
@@ -184,7 +200,7 @@ struct RejectShared {
 // fp32 hi/lo pair inside fused multiply-adds).
 __device__ __forceinline__ void stats_block(const RejectParams &p, int row, int seg, RejectShared &sh)
 {
-    constexpr int UNROLL = 4;
+    constexpr int UNROLL = 8;   // 128 bytes per thread in flight
     const int tid = threadIdx.x;
     const float *base = row < p.T ? p.target_logits + (size_t)row * p.V
                                   : p.draft_logits + (size_t)(row - p.T) * p.V;
@@ -241,12 +257,12 @@ __device__ __forceinline__ void stats_block(const RejectParams &p, int row, int 
         double total = 0.0;
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) total += sh.red_d[w];
-        // word 0: the sum; word 1: offset | generation tag, written once word 0 is in memory,
-        // so whoever sees this call's tag in word 1 may read word 0
-        unsigned long long *dst = reinterpret_cast<unsigned long long *>(p.stats + (size_t)row * p.stat_segments + seg);
-        publish_u64(dst + 0, (unsigned long long)__double_as_longlong(total));
-        writes_complete();
-        publish_u64(dst + 1, (unsigned long long)__float_as_uint(boff) | ((unsigned long long)p.generation << 32));
+        // three tagged words: low and high half of the fp64 sum, and the offset
+        unsigned long long *dst = p.stats + 3 * ((size_t)row * p.stat_segments + seg);
+        const unsigned long long bits = (unsigned long long)__double_as_longlong(total);
+        publish_tagged(dst + 0, (uint32_t)bits, p.generation);
+        publish_tagged(dst + 1, (uint32_t)(bits >> 32), p.generation);
+        publish_tagged(dst + 2, __float_as_uint(boff), p.generation);
     }
 }
 
@@ -376,28 +392,22 @@ __device__ bool accept_phase(const RejectParams &p, int b, RejectShared &sh, boo
         dx = p.draft_logits[(size_t)(row_d0 + tid) * p.V + x];
     }
 
-    auto stat_words = [&](int i) {
-        const int ri = i / p.stat_segments;
-        const int sg = i - ri * p.stat_segments;
-        const int row = ri <= k ? row_t0 + ri : p.T + row_d0 + (ri - k - 1);
-        return reinterpret_cast<const unsigned long long *>(p.stats + (size_t)row * p.stat_segments + sg);
-    };
+    // poll and fetch in one: every word carries its own tag
     const bool ok = wait_all(p.spin_limit, [&] {
         bool mine = true;
-        for (int i = tid; i < nstat; i += kThreads)
-            mine = mine && ((uint32_t)(fetch_u64(stat_words(i) + 1) >> 32) == p.generation);
+        for (int i = tid; i < nstat; i += kThreads) {
+            const int ri = i / p.stat_segments;
+            const int sg = i - ri * p.stat_segments;
+            const int row = ri <= k ? row_t0 + ri : p.T + row_d0 + (ri - k - 1);
+            const unsigned long long *st = p.stats + 3 * ((size_t)row * p.stat_segments + sg);
+            const unsigned long long w0 = fetch_u64(st), w1 = fetch_u64(st + 1), w2 = fetch_u64(st + 2);
+            mine = mine && tagged_ok(w0, p.generation) && tagged_ok(w1, p.generation) && tagged_ok(w2, p.generation);
+            sh.seg_sum[ri][sg] = __longlong_as_double((long long)((w0 & 0xFFFFFFFFull) | (w1 << 32)));
+            sh.seg_off[ri][sg] = __uint_as_float((uint32_t)w2);
+        }
         return mine;
     });
     if (!ok) return false;
-    order_after_ticket();
-    for (int i = tid; i < nstat; i += kThreads) {
-        const unsigned long long *st = stat_words(i);
-        const int ri = i / p.stat_segments;
-        const int sg = i - ri * p.stat_segments;
-        sh.seg_sum[ri][sg] = __longlong_as_double((long long)fetch_u64(st));
-        sh.seg_off[ri][sg] = __uint_as_float((uint32_t)fetch_u64(st + 1));
-    }
-    __syncthreads();
     if (tid < nrows) {
         float mx = kEmptyMax;
         for (int sg = 0; sg < p.stat_segments; ++sg) mx = fmaxf(mx, sh.seg_off[tid][sg]);
@@ -476,12 +486,10 @@ __device__ __forceinline__ RaceRows race_rows(const RejectParams &p, int b, cons
     return rr;
 }
 
-// One (request, vocabulary segment) of the race.  Race items come after every
-// statistics item and every attention item in the grid, so when one is scheduled
-// its request's statistics have normally long been published; the bounded wait in
-// accept_phase only matters for launches with little else to do.  The statistics
-// blocks it waits for never wait themselves and precede it in dispatch order, so
-// the wait ends; should it ever run out, the request's outputs are set to -1.
+// One (request, vocabulary segment) of the race.  Race items follow all statistics
+// items in the grid, so the statistics blocks they wait for (inside accept_phase, with
+// a bound) were scheduled before them and never wait themselves: the wait ends.
+// Should the bound ever run out, the request's outputs are set to -1.
 __device__ void race_role(const RejectParams &p, int item, RejectShared &sh)
 {
     const int tid = threadIdx.x;
@@ -499,13 +507,15 @@ __device__ void race_role(const RejectParams &p, int item, RejectShared &sh)
     race_segment(p, rr.trow, rr.drow, b, v0, v1, rr.off_t, rr.corr_t, rr.off_d, rr.corr_d, sh, win_score, win_id);
     if (tid == 0) {
         unsigned long long *dst = p.race_partial + 2 * ((size_t)b * p.race_segments + seg);
-        publish_u64(dst + 0, ((unsigned long long)__float_as_uint(win_score) << 32) | (unsigned long long)(uint32_t)win_id);
-        writes_complete();
-        publish_u64(dst + 1, (unsigned long long)p.generation << 32);
+        publish_tagged(dst + 0, __float_as_uint(win_score), p.generation);
+        publish_tagged(dst + 1, (uint32_t)win_id, p.generation);
+        if (seg == 0)   // the accept chain's result, for the final stage
+            publish_tagged(p.race_info + b, (uint32_t)rr.m | ((uint32_t)rr.k << 8) | ((uint32_t)sh.near << 16),
+                           p.generation);
     }
 }
 
-// Last stage of request b (one item per request at the very end of the grid):
+// Last stage of request b (one item per request, after all race items):
 // waits (bounded) for the request's race segments, picks the winner, writes the
 // outputs and counters, and clears the request's tags so that a replay of the
 // same launch (HIP graph) starts clean.
@@ -513,23 +523,31 @@ __device__ void final_role(const RejectParams &p, int b, RejectShared &sh)
 {
     const int tid = threadIdx.x;
     unsigned long long *part = p.race_partial + 2 * (size_t)b * p.race_segments;
+    // poll and fetch in one: the race partials (race_segments <= 64: wavefront 0 holds
+    // them all) and the accept chain's result
+    float best_score = -1.0f;
+    int best_id = 0x7FFFFFFF;
+    uint32_t info = 0;
     const bool ok = wait_all(p.spin_limit, [&] {
-        return tid >= p.race_segments || (uint32_t)(fetch_u64(part + 2 * tid + 1) >> 32) == p.generation;
+        bool mine = true;
+        if (tid < p.race_segments) {
+            const unsigned long long w0 = fetch_u64(part + 2 * tid), w1 = fetch_u64(part + 2 * tid + 1);
+            mine = tagged_ok(w0, p.generation) && tagged_ok(w1, p.generation);
+            best_score = __uint_as_float((uint32_t)w0);
+            best_id = (int)(uint32_t)w1;
+        }
+        if (tid == 0) {
+            const unsigned long long wi = fetch_u64(p.race_info + b);
+            mine = mine && tagged_ok(wi, p.generation);
+            info = (uint32_t)wi;
+        }
+        return mine;
     });
-    if (!ok || !accept_phase(p, b, sh, false)) {
+    if (!ok) {
         if (tid == 0) { p.accepted_len[b] = -1; p.next_token[b] = -1; }
         return;
     }
-    order_after_ticket();
-    const RaceRows rr = race_rows(p, b, sh);
-
-    float best_score = -1.0f;
-    int best_id = 0x7FFFFFFF;
-    if (tid < p.race_segments) {   // race_segments <= 64: wavefront 0 holds them all
-        const unsigned long long v = fetch_u64(part + 2 * tid);
-        best_score = __uint_as_float((uint32_t)(v >> 32));
-        best_id = (int)(uint32_t)v;
-    }
+    if (tid == 0) sh.m = (int)info;
 #pragma unroll
     for (int o = kWave / 2; o > 0; o >>= 1) {
         const float os = __shfl_xor(best_score, o);
@@ -540,37 +558,46 @@ __device__ void final_role(const RejectParams &p, int b, RejectShared &sh)
     __syncthreads();
     float win_score = sh.best_score[0];
     int win_id = sh.best_id[0];
+    info = (uint32_t)sh.m;
     __syncthreads();
+    const int m = (int)(info & 0xFFu), k = (int)((info >> 8) & 0xFFu), near = (int)(info >> 16);
+    const int row_t0 = p.cu_q_len[b];
+    const int row_d0 = row_t0 - b;
     if (!(win_score > 0.0f)) {
         // p - q has no positive entry (p == q to rounding): draw from p instead
+        if (!accept_phase(p, b, sh, false)) {
+            if (tid == 0) { p.accepted_len[b] = -1; p.next_token[b] = -1; }
+            return;
+        }
+        const RaceRows rr = race_rows(p, b, sh);
         race_segment(p, rr.trow, nullptr, b, 0, p.V, rr.off_t, rr.corr_t, 0.0f, 0.0f, sh, win_score, win_id);
     }
-    const int m = rr.m, k = rr.k;
     if (tid == 0) {
         p.accepted_len[b] = m;
         p.next_token[b] = win_id;
         if (p.out_tokens != nullptr) {
             int32_t *row = p.out_tokens + (size_t)b * (SPEC_K_MAX + 1);
             for (int i = 0; i <= SPEC_K_MAX; ++i)
-                row[i] = i < m ? p.draft_tokens[rr.row_d0 + i] : (i == m ? win_id : -1);
+                row[i] = i < m ? p.draft_tokens[row_d0 + i] : (i == m ? win_id : -1);
         }
         atomicAdd(&p.counters[0], (unsigned long long)k);
         atomicAdd(&p.counters[1], (unsigned long long)m);
         atomicAdd(&p.counters[2], (unsigned long long)(m + 1 < k ? m + 1 : k));
         atomicAdd(&p.counters[3], (unsigned long long)(m + 1));
-        atomicAdd(&p.counters[4], (unsigned long long)sh.near);
+        atomicAdd(&p.counters[4], (unsigned long long)near);
         atomicAdd(&p.counters[5], 1ull);
     }
     // clear this request's tags
-    const int row_t0 = p.cu_q_len[b];
     const int nstat = (2 * k + 1) * p.stat_segments;
-    for (int i = tid; i < nstat; i += kThreads) {
-        const int ri = i / p.stat_segments;
-        const int sg = i - ri * p.stat_segments;
-        const int row = ri <= k ? row_t0 + ri : p.T + rr.row_d0 + (ri - k - 1);
-        publish_u64(reinterpret_cast<unsigned long long *>(p.stats + (size_t)row * p.stat_segments + sg) + 1, 0ull);
+    for (int i = tid; i < 3 * nstat; i += kThreads) {
+        const int rec = i / 3;
+        const int ri = rec / p.stat_segments;
+        const int sg = rec - ri * p.stat_segments;
+        const int row = ri <= k ? row_t0 + ri : p.T + row_d0 + (ri - k - 1);
+        publish_u64(p.stats + 3 * ((size_t)row * p.stat_segments + sg) + (i - 3 * rec), 0ull);
     }
-    if (tid < p.race_segments) publish_u64(part + 2 * tid + 1, 0ull);
+    if (tid < 2 * p.race_segments) publish_u64(part + tid, 0ull);
+    if (tid == 0) publish_u64(p.race_info + b, 0ull);
 }
 
 // ===========================================================================
@@ -602,6 +629,11 @@ __device__ void attn_role(const AttnParams &p, int item, AttnShared<NT> &sh)
     const int kvh = unit % p.Hkv;
     const int b = unit / p.Hkv;
 
+    // When no request is split, a wavefront's block-table entries do not depend on kv_len:
+    // fetch them alongside it (entries past the request's pages are never used).
+    int bt = 0;
+    if (p.max_chunks == 1 && wave + kWaves * lane < p.max_blocks_per_req)
+        bt = p.block_table[(size_t)b * p.max_blocks_per_req + wave + kWaves * lane];
     const int L = p.kv_len[b];
     const int nchunks = (L + p.chunk_tokens - 1) / p.chunk_tokens;
     if (chunk >= nchunks) return;
@@ -617,8 +649,7 @@ __device__ void attn_role(const AttnParams &p, int item, AttnShared<NT> &sh)
     const int page0 = tok0 / SPEC_BLOCK_SIZE;
 
     // block-table entries of this wavefront's pages (wave, wave+4, ...), one per lane
-    int bt = 0;
-    if (wave + kWaves * lane < npages)
+    if (p.max_chunks != 1 && wave + kWaves * lane < npages)
         bt = p.block_table[(size_t)b * p.max_blocks_per_req + page0 + wave + kWaves * lane];
 
     // Q as the B operand of S^T = K Q^T, and each lane's last visible key
@@ -642,26 +673,30 @@ __device__ void attn_role(const AttnParams &p, int item, AttnShared<NT> &sh)
         out_row[nt] = valid ? (int)rh : -1;
     }
 
-    const char *kbase = static_cast<const char *>(p.k_cache) + (size_t)kvh * kPageHeadBytes + lane * 16;
-    const char *vbase = static_cast<const char *>(p.v_cache) + (size_t)kvh * kPageHeadBytes + lane * 16;
+    // Pages are read with buffer loads through a descriptor that covers exactly one
+    // (page, KV head): 4 KB of K or V.  A page index past the end gets a descriptor of
+    // length 0, for which the hardware returns zeros without touching memory.  That
+    // keeps every load unconditional, so the loads of later pages stay in flight across
+    // the arithmetic of the current one (a branch around them would make the compiler
+    // wait for all outstanding loads at every use).
+    const char *khead = static_cast<const char *>(p.k_cache) + (size_t)kvh * kPageHeadBytes;
+    const char *vhead = static_cast<const char *>(p.v_cache) + (size_t)kvh * kPageHeadBytes;
     const size_t page_stride = (size_t)p.Hkv * kPageHeadBytes;
+    const int my_pages = npages > wave ? (npages - wave + kWaves - 1) / kWaves : 0;   // pages wave, wave+4, ...
+    const int lane_off = lane * 16;
 
-    auto load_page = [&](int pi, PageRegs &r) {
-        if (pi < npages) {
-            const int page = __builtin_amdgcn_readlane(bt, pi >> 2);   // pi = wave + 4 * (lane index)
-            const char *kp = kbase + (size_t)page * page_stride;
-            const char *vp = vbase + (size_t)page * page_stride;
+    auto load_page = [&](int it, PageRegs &r) {   // it-th page of this wavefront
+        const bool valid = it < my_pages;
+        const int page = __builtin_amdgcn_readlane(bt, valid ? it : 0);
+        const int bytes = valid ? kPageHeadBytes : 0;
+        const __amdgpu_buffer_rsrc_t kd = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<char *>(khead + (size_t)page * page_stride), 0, bytes, kBufferFlags);
+        const __amdgpu_buffer_rsrc_t vd = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<char *>(vhead + (size_t)page * page_stride), 0, bytes, kBufferFlags);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) r.k[i] = *reinterpret_cast<const u32x4 *>(kp + i * 1024);
+        for (int i = 0; i < 4; ++i) r.k[i] = __builtin_amdgcn_raw_buffer_load_b128(kd, lane_off, i * 1024, 0);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) r.v[i] = *reinterpret_cast<const u32x4 *>(vp + i * 1024);
-        } else {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                r.k[i] = (u32x4){0, 0, 0, 0};
-                r.v[i] = (u32x4){0, 0, 0, 0};
-            }
-        }
+        for (int i = 0; i < 4; ++i) r.v[i] = __builtin_amdgcn_raw_buffer_load_b128(vd, lane_off, i * 1024, 0);
     };
 
     f32x4 acc[NT][8];
@@ -676,18 +711,16 @@ __device__ void attn_role(const AttnParams &p, int item, AttnShared<NT> &sh)
 
     const int first_masked_token = L - q_len + 1;  // keys from here on are hidden from some row (or past the end)
 
-    PageRegs cur;
-    load_page(wave, cur);
-    for (int pi = wave; pi < npages; pi += kWaves) {
-        PageRegs nxt;
-        load_page(pi + kWaves, nxt);
-
+    // Software pipeline: the loads of the next DEPTH pages are in flight while a page is
+    // consumed.  The ring is indexed statically (the loop is unrolled by its length).
+    auto consume = [&](PageRegs &cur, int pi) {
         const int page_tok = tok0 + pi * SPEC_BLOCK_SIZE;
         const bool need_mask = page_tok + SPEC_BLOCK_SIZE > first_masked_token;
         const int tbase = page_tok + 4 * g;
 
-        if (page_tok + SPEC_BLOCK_SIZE > L) {
-            // last page of the request: slots past kv_len may hold anything; clear their V
+        {
+            // slots past kv_len in the request's last page may hold anything: clear their V
+            // (done on every page, without a branch, so that no load has to be waited for early)
             const int nvalid = min(max(L - tbase, 0), 4);
             const uint32_t lo = nvalid >= 2 ? 0xFFFFFFFFu : (nvalid == 1 ? 0x0000FFFFu : 0u);
             const uint32_t hi = nvalid >= 4 ? 0xFFFFFFFFu : (nvalid == 3 ? 0x0000FFFFu : 0u);
@@ -736,7 +769,39 @@ __device__ void attn_role(const AttnParams &p, int item, AttnShared<NT> &sh)
                 if (SPLIT_P) acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va, p_lo, acc[nt][mt], 0, 0, 0);
             }
         }
-        cur = nxt;
+    };
+
+    // Two register batches of P pages each.  While one batch is consumed the loads of the
+    // other are in flight.  The order inside a half-step matters: first wait for the batch
+    // about to be consumed (at that point it is the only one outstanding, so the full
+    // wait the compiler emits waits for nothing else), then issue the other batch's loads,
+    // then do the arithmetic, which needs no further wait.
+    constexpr int P = NT == 1 ? 2 : 1;   // by register budget
+    PageRegs batch_a[P], batch_b[P];
+    auto load_batch = [&](int it, PageRegs(&r)[P]) {
+#pragma unroll
+        for (int j = 0; j < P; ++j) load_page(it + j, r[j]);
+    };
+    auto arrived = [&](PageRegs(&r)[P]) {
+#pragma unroll
+        for (int j = 0; j < P; ++j)
+            asm volatile("" ::"v"(r[j].k[0]), "v"(r[j].k[1]), "v"(r[j].k[2]), "v"(r[j].k[3]), "v"(r[j].v[0]),
+                         "v"(r[j].v[1]), "v"(r[j].v[2]), "v"(r[j].v[3])
+                         : "memory");
+    };
+    auto consume_batch = [&](PageRegs(&r)[P], int it) {
+#pragma unroll
+        for (int j = 0; j < P; ++j)
+            if (it + j < my_pages) consume(r[j], wave + kWaves * (it + j));
+    };
+    load_batch(0, batch_a);
+    for (int it0 = 0; it0 < my_pages; it0 += 2 * P) {
+        arrived(batch_a);
+        load_batch(it0 + P, batch_b);
+        consume_batch(batch_a, it0);
+        arrived(batch_b);
+        load_batch(it0 + 2 * P, batch_a);
+        consume_batch(batch_b, it0 + P);
     }
 
     // each lane summed its own four tokens per page: finish the row sums
@@ -866,36 +931,60 @@ __device__ void attn_role(const AttnParams &p, int item, AttnShared<NT> &sh)
 // ===========================================================================
 // The kernel
 // ===========================================================================
-template <int NT, bool HAS_ATTN, bool HAS_REJECT>
-__global__ __launch_bounds__(kThreads, 2) void spec_step_kernel(AttnParams ap, RejectParams rp, int n_stat_items,
-                                                                 int n_attn_items)
+// Grid order.  The n_reject rejection items (statistics, then race, then final) are
+// spread evenly among the n_attn attention items, keeping their own order: at any
+// time only a fraction of the resident blocks belongs to the latency-bound rejection
+// stages, the rest keep streaming the KV cache, and the rejection half is done well
+// before the attention half.  Position i holds an attention item iff
+// floor((i+1) * n_attn / n) > floor(i * n_attn / n).
+struct GridSplit {
+    int n_stat, n_reject, n_attn;
+};
+
+template <int NT, bool HAS_ATTN, bool HAS_REJECT, bool SPLIT_P>
+__global__ __launch_bounds__(kThreads, 2) void spec_step_kernel(AttnParams ap, RejectParams rp, GridSplit gs)
 {
-    const int item = blockIdx.x;
+    int item = blockIdx.x;
+    bool is_attn = HAS_ATTN;
+    if constexpr (HAS_ATTN && HAS_REJECT) {
+        const long long n = (long long)gs.n_reject + gs.n_attn;
+        const int before = (int)(((long long)item * gs.n_attn) / n);
+        const int upto = (int)(((long long)(item + 1) * gs.n_attn) / n);
+        is_attn = upto > before;
+        item = is_attn ? before : item - before;
+    }
     if constexpr (HAS_REJECT) {
-        __shared__ RejectShared rsh;
-        if (item < n_stat_items) {
-            stats_role(rp, item, rsh);
-            return;
-        }
-        const int after = item - n_stat_items - n_attn_items;
-        if (after >= 0) {
-            const int n_race = rp.B * rp.race_segments;
-            if (after < n_race) race_role(rp, after, rsh);
-            else final_role(rp, after - n_race, rsh);
+        if (!is_attn) {
+            __shared__ RejectShared rsh;
+            if (item < gs.n_stat) {
+                stats_role(rp, item, rsh);
+            } else {
+                const int after = item - gs.n_stat;
+                const int n_race = rp.B * rp.race_segments;
+                if (after < n_race) race_role(rp, after, rsh);
+                else final_role(rp, after - n_race, rsh);
+            }
             return;
         }
     }
     if constexpr (HAS_ATTN) {
         __shared__ AttnShared<NT> ash;
-        attn_role<NT, true>(ap, item - n_stat_items, ash);
+        attn_role<NT, SPLIT_P>(ap, item, ash);
     }
 }
 
 template <int NT, bool HAS_ATTN, bool HAS_REJECT>
 hipError_t launch(const AttnParams &ap, const RejectParams &rp, int n_stat, int n_attn, int n_race, hipStream_t stream)
 {
-    hipLaunchKernelGGL((spec_step_kernel<NT, HAS_ATTN, HAS_REJECT>), dim3(n_stat + n_attn + n_race), dim3(kThreads), 0,
-                       stream, ap, rp, n_stat, n_attn);
+    GridSplit gs;
+    gs.n_stat = n_stat;
+    gs.n_reject = n_stat + n_race;
+    gs.n_attn = n_attn;
+    const dim3 grid(n_stat + n_race + n_attn);
+    if (HAS_ATTN && !ap.split_p)
+        hipLaunchKernelGGL((spec_step_kernel<NT, HAS_ATTN, HAS_REJECT, false>), grid, dim3(kThreads), 0, stream, ap, rp, gs);
+    else
+        hipLaunchKernelGGL((spec_step_kernel<NT, HAS_ATTN, HAS_REJECT, true>), grid, dim3(kThreads), 0, stream, ap, rp, gs);
     return hipGetLastError();
 }
 
