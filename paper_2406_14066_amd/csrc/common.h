@@ -16,22 +16,22 @@ constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kEmptyMax = -1.0e30f;  // running maximum of a row that has seen no key yet
 
 // ---------------------------------------------------------------- attention
-// Partial results in the workspace (both attention kernels):
+// Split of the KV length.  A request of L tokens is cut into
+// nch = ceil(L / chunk_tokens) chunks.  The generic kernel uses chunks of exactly
+// chunk_tokens; the matrix-instruction kernel evens them out per request
+// (chunk = ceil(L / nch) rounded up to 64 tokens).  Each (query row, query head,
+// chunk) owns one partial result in the workspace:
 //   acc  [T*Hq][max_chunks][d]  un-normalised sum_t 2^(s_t - m) V_t
 //   ml   [T*Hq][max_chunks][2]  running maximum m (base-2 units) and sum l of 2^(s_t - m)
-// Generic kernel: a request of L tokens is cut into ceil(L / chunk_tokens) chunks of
-// exactly chunk_tokens tokens; slot index = chunk index.
-// Matrix-instruction kernel: the page sequence of the whole batch is dealt to `workers`
-// wavefronts; slot index = index of the segment within its (request, KV head);
-// tickets [B*Hkv] count the segments of a (request, KV head) that have been delivered.
+// tickets [B*Hkv] count the chunks of a (request, KV head) that have finished;
+// the block that finishes last merges the partials (matrix-instruction kernel).
 struct AttnPlan {
-    int32_t chunk_tokens;  // generic kernel
-    int32_t max_chunks;    // slots per (query row, head)
+    int32_t chunk_tokens;
+    int32_t max_chunks;
     int32_t max_q_len;
     int32_t use_mfma;      // 1: bf16 matrix-instruction kernel, 0: generic kernel
     int32_t row_tiles;     // 16-row tiles covering max_q_len * (Hq/Hkv) rows (mfma kernel)
-    int32_t workers;       // wavefronts streaming the KV cache (mfma kernel)
-    int32_t fused_combine; // mfma kernel merges the partials itself (few segments) or leaves it to a combine launch
+    int32_t fused_combine; // mfma kernel merges the chunk partials itself (few chunks) or leaves it to the combine kernel
     size_t acc_bytes;
     size_t ml_bytes;
     size_t ticket_bytes;
@@ -42,7 +42,6 @@ struct AttnParams {
     int32_t B, Hq, Hkv, d, num_blocks, max_blocks_per_req, T;
     int32_t kv_layout;
     int32_t chunk_tokens, max_chunks;
-    int32_t workers;
     float scale_log2;  // softmax scale times log2(e): scores are kept in base-2 units
     const void *q, *k_cache, *v_cache;
     const int32_t *block_table, *kv_len, *cu_q_len;
@@ -51,9 +50,10 @@ struct AttnParams {
     float *ws_ml;
     unsigned long long *tickets;
     uint32_t generation;  // tags this call's ticket values, never 0
-    int32_t fused_combine;
+    int32_t fused_combine;        // matrix kernel: the last chunk's block merges the partials (needs max_chunks <= 16)
+    int32_t attn_first_limit;     // attention blocks go first in the grid when there are at most this many
     int32_t split_p;              // feed the softmax weights to the PV product as bf16 high + low parts
-    int32_t single_chunk_direct;  // generic combine kernel: skip requests with one chunk (unused by the generic path)
+    int32_t single_chunk_direct;  // requests with one chunk were written straight to `out`: the combine kernel skips them
 };
 
 // ---------------------------------------------------------------- rejection
@@ -97,7 +97,6 @@ hipError_t launch_step_fused(const AttnParams *attn, int row_tiles, const Reject
 // Generic attention path: partial kernel + combine kernel.
 hipError_t launch_attn_generic(const AttnParams &p, int dtype, hipStream_t stream);
 hipError_t launch_attn_combine(const AttnParams &p, hipStream_t stream);
-hipError_t launch_attn_combine_segments(const AttnParams &p, hipStream_t stream);
 hipError_t launch_kv_repack(const void *src_k, const void *src_v, void *dst_k, void *dst_v, int32_t num_blocks,
                             int32_t Hkv, int32_t d, hipStream_t stream);
 

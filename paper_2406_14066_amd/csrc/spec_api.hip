@@ -92,6 +92,10 @@ spec_status validate_reject(const spec_reject_args *r)
     return SPEC_OK;
 }
 
+// Split of the KV length.  The matrix-instruction kernel runs one block per
+// (request, KV head, chunk); the chunk is sized so that the launch has about
+// eight blocks per compute unit, in multiples of the 64 tokens a block's four
+// wavefronts take per round.
 // Number of compute units of the current device (cached per process; one GPU).
 int compute_units()
 {
@@ -106,17 +110,13 @@ int compute_units()
     return cached;
 }
 
-// Matrix-instruction kernel: one attention block (four wavefronts) per compute unit; the
-// batch's page sequence is dealt evenly to the wavefronts.  Generic kernel: chunks of 256 keys.
 AttnPlan plan_attn(const spec_attn_args *a)
 {
     AttnPlan pl;
     memset(&pl, 0, sizeof pl);
     int max_len = 0, max_q = 0;
-    int64_t pages = 0;
     for (int b = 0; b < a->B; ++b) {
         if (a->host_kv_len[b] > max_len) max_len = a->host_kv_len[b];
-        pages += (a->host_kv_len[b] + SPEC_BLOCK_SIZE - 1) / SPEC_BLOCK_SIZE;
         const int q_len = a->host_cu_q_len[b + 1] - a->host_cu_q_len[b];
         if (q_len > max_q) max_q = q_len;
     }
@@ -124,32 +124,36 @@ AttnPlan plan_attn(const spec_attn_args *a)
     const int group = a->Hq / a->Hkv;
     const int rows = max_q * group;
     pl.row_tiles = (rows + 15) / 16;
-    pl.use_mfma = (a->qkv_dtype == SPEC_BF16 && a->kv_layout == SPEC_KV_MFMA && a->d == 128 && pl.row_tiles <= 3 &&
-                   a->B <= 4096) ? 1 : 0;
+    pl.use_mfma = (a->qkv_dtype == SPEC_BF16 && a->kv_layout == SPEC_KV_MFMA && a->d == 128 && pl.row_tiles <= 3) ? 1 : 0;
     // diagnostic switch: SPEC_VERIFY_FORCE_GENERIC=1 routes every shape through the generic kernel
     const char *force = getenv("SPEC_VERIFY_FORCE_GENERIC");
     if (force != nullptr && force[0] == '1') pl.use_mfma = 0;
     if (pl.use_mfma) {
-        int blocks = compute_units();
-        if (const char *t = getenv("SPEC_VERIFY_ATTN_BLOCKS")) {   // tuning switch
+        // One block per (request, KV head, chunk).  Splitting costs (partials, a merge, more
+        // block start-ups), so the longest request is split only as far as needed to give every
+        // compute unit a block.
+        long target_blocks = compute_units();
+        if (const char *t = getenv("SPEC_VERIFY_TARGET_BLOCKS")) {   // tuning switch
             const long v = strtol(t, nullptr, 10);
-            if (v >= 1 && v <= 65536) blocks = (int)v;
+            if (v >= 1 && v <= (1 << 20)) target_blocks = v;
         }
-        const int64_t total_pages = pages * a->Hkv;
-        // never more workers than pages: every worker then owns at least one page and the
-        // segments of a (request, KV head) belong to consecutive workers
-        pl.workers = (int32_t)(total_pages < 4 * (int64_t)blocks ? total_pages : 4 * (int64_t)blocks);
-        // a worker's share is at least floor(total / workers) pages, so a (request, KV head) of n
-        // pages meets at most ceil(n / share) + 1 workers
-        const int64_t share = total_pages / pl.workers;
-        const int64_t max_pages = (max_len + SPEC_BLOCK_SIZE - 1) / SPEC_BLOCK_SIZE;
-        pl.max_chunks = share >= 1 ? (int32_t)((max_pages + share - 1) / share + 1) : (int32_t)max_pages;
-        pl.fused_combine = pl.max_chunks <= 16 ? 1 : 0;
-        pl.chunk_tokens = 0;
+        const int64_t units = (int64_t)a->B * a->Hkv;
+        int64_t nsplit = (target_blocks + units - 1) / units;
+        if (nsplit < 1) nsplit = 1;
+        int64_t chunk = (max_len + nsplit - 1) / nsplit;
+        chunk = (chunk + SPEC_BLOCK_SIZE - 1) / SPEC_BLOCK_SIZE * SPEC_BLOCK_SIZE;
+        if (chunk < 64) chunk = 64;
+        if (chunk > 4096) chunk = 4096;  // a wavefront holds its pages' block-table entries one per lane
+        if (const char *forced = getenv("SPEC_VERIFY_CHUNK")) {      // tuning switch: tokens, multiple of 16
+            const long v = strtol(forced, nullptr, 10);
+            if (v >= 16 && v <= 4096 && v % SPEC_BLOCK_SIZE == 0) chunk = v;
+        }
+        pl.chunk_tokens = (int32_t)chunk;
     } else {
         pl.chunk_tokens = 256;  // one key per thread of the generic kernel
-        pl.max_chunks = (max_len + pl.chunk_tokens - 1) / pl.chunk_tokens;
     }
+    pl.max_chunks = (max_len + pl.chunk_tokens - 1) / pl.chunk_tokens;
+    pl.fused_combine = (pl.use_mfma && pl.max_chunks <= 16) ? 1 : 0;
     const size_t slots = (size_t)a->T * a->Hq * pl.max_chunks;
     pl.acc_bytes = align_up(slots * a->d * sizeof(float));
     pl.ml_bytes = align_up(slots * 2 * sizeof(float));
@@ -215,7 +219,6 @@ AttnParams attn_params(const spec_attn_args *a, const AttnPlan &pl, char *ws)
     p.num_blocks = a->num_blocks; p.max_blocks_per_req = a->max_blocks_per_req; p.T = a->T;
     p.kv_layout = a->kv_layout;
     p.chunk_tokens = pl.chunk_tokens; p.max_chunks = pl.max_chunks;
-    p.workers = pl.workers;
     const double scale = a->softmax_scale > 0.0f ? (double)a->softmax_scale : 1.0 / sqrt((double)a->d);
     p.scale_log2 = (float)(scale * kLog2eD);
     p.q = a->q; p.k_cache = a->k_cache; p.v_cache = a->v_cache;
@@ -226,8 +229,9 @@ AttnParams attn_params(const spec_attn_args *a, const AttnPlan &pl, char *ws)
     p.tickets = reinterpret_cast<unsigned long long *>(ws + pl.acc_bytes + pl.ml_bytes);
     p.generation = next_generation();
     p.fused_combine = pl.fused_combine;
-    p.single_chunk_direct = 0;
+    p.single_chunk_direct = pl.use_mfma;
     p.split_p = 1;
+    p.attn_first_limit = 2 * compute_units();   // two blocks fit on a compute unit
     if (const char *e = getenv("SPEC_VERIFY_SPLIT_P")) p.split_p = (e[0] != '0');   // experiment switch
     return p;
 }
@@ -303,7 +307,7 @@ spec_status spec_verify_attn(const spec_attn_args *attn, void *workspace, size_t
     hipError_t err =
         timed(SPEC_KERNEL_ATTN, stream, [&] { return launch_step_fused(&ap, pl.row_tiles, nullptr, stream); });
     if (err == hipSuccess && !pl.fused_combine && pl.max_chunks > 1)
-        err = timed(SPEC_KERNEL_ATTN_COMBINE, stream, [&] { return launch_attn_combine_segments(ap, stream); });
+        err = timed(SPEC_KERNEL_ATTN_COMBINE, stream, [&] { return launch_attn_combine(ap, stream); });
     return err == hipSuccess ? SPEC_OK : SPEC_EHIP;
 }
 
@@ -342,7 +346,7 @@ spec_status spec_verify_step(const spec_attn_args *attn, const spec_reject_args 
         hipError_t err =
             timed(SPEC_KERNEL_STEP, stream, [&] { return launch_step_fused(&ap, apl.row_tiles, &rp, stream); });
         if (err == hipSuccess && !apl.fused_combine && apl.max_chunks > 1)
-            err = timed(SPEC_KERNEL_ATTN_COMBINE, stream, [&] { return launch_attn_combine_segments(ap, stream); });
+            err = timed(SPEC_KERNEL_ATTN_COMBINE, stream, [&] { return launch_attn_combine(ap, stream); });
         return err == hipSuccess ? SPEC_OK : SPEC_EHIP;
     }
     st = run_attn_generic(ap, attn->qkv_dtype, stream);

@@ -12,10 +12,12 @@
 //                its segment for the next token.
 //   final        one per request: picks the race winner, writes the request's
 //                outputs and counters.
-//   attention    one block per compute unit, first in the grid; its wavefronts each
-//                stream an equal share of the KV cache (see "Attention half").
-// The rejection items follow the attention blocks in the grid and run in the second
-// block slot of each compute unit, underneath the attention stream.
+//   attention    one (request, KV head, KV chunk) each; the block that completes
+//                the LAST chunk of a (request, KV head) merges the chunk partials
+//                and writes the output.
+// The rejection items keep that order among themselves and are spread evenly among
+// the attention items (see GridSplit), so that the rejection half, whose stages
+// depend on each other, runs underneath the long attention stream.
 //
 // Attention blocks never wait: "last one out merges" is decided with one atomic
 // ticket per (request, KV head).  Race and final items consume what earlier items
@@ -292,7 +294,7 @@ __device__ void race_segment(const RejectParams &p, const float *target_row, con
     int best_id = 0x7FFFFFFF;
     const int g_begin = v0 >> 2, g_end = v1 >> 2;
     const uint32_t c3 = (p.step_hi24 << 8) | 1u;
-    constexpr int U = 4;  // row vectors in flight per thread
+    constexpr int U = 2;  // row vectors in flight per thread
     for (int g0 = g_begin + threadIdx.x; g0 < g_end; g0 += kThreads * U) {
         float4 xt[U], xd[U];
 #pragma unroll
@@ -363,7 +365,7 @@ __device__ __forceinline__ bool wait_all(int spin_limit, F probe)
 {
     for (int spin = 0; spin < spin_limit; ++spin) {
         if (__syncthreads_and(probe() ? 1 : 0)) return true;
-        __builtin_amdgcn_s_sleep(8);
+        __builtin_amdgcn_s_sleep(32);
     }
     return false;
 }
@@ -600,337 +602,268 @@ __device__ void final_role(const RejectParams &p, int b, RejectShared &sh)
 
 // ===========================================================================
 // Attention half
-//
-// Work decomposition: the KV cache to be read is one long sequence of
-// (request, KV head, page) triples, request-major, then KV head, then page.  It is
-// cut into `workers` equal contiguous ranges, one per wavefront of the attention
-// blocks (there is one attention block per compute unit, placed first in the grid,
-// so every compute unit streams the same number of bytes).  A range is walked as
-// a list of segments, a segment being the part of one (request, KV head) that falls
-// into the range.  A (request, KV head) that lies wholly inside one range is
-// finished by that wavefront alone and written straight to the output; one that
-// is spread over several ranges gets a partial per segment, and the wavefront
-// that delivers its last segment merges them (or a separate combine kernel does,
-// when there are too many segments to merge in place).
 // ===========================================================================
 struct PageRegs {
     u32x4 k[4];  // k[kk]: token n, dims 32*kk + 8g .. +7
     u32x4 v[4];  // v[pp]: dims 32*pp + n (low half) and 32*pp + 16 + n (high half), tokens 4g .. 4g+3
 };
 
-constexpr int kMaxScanRequests = 4096;   // requests whose page counts fit the block's prefix-sum table
-
+template <int NT>
 struct AttnShared {
-    int cum_pages[kMaxScanRequests + 1];   // exclusive prefix sum of ceil(kv_len / 16)
-    int wave_total[kWaves];
+    f32x4 acc[2][NT][8][kWave];
+    float m[2][NT][kWave];
+    float l[2][NT][kWave];
+    int last;
 };
 
-// pages [first, end) of worker w when `total` pages are dealt to `workers` workers
-__device__ __forceinline__ long long worker_begin(long long w, long long total, int workers)
-{
-    return (w * total) / workers;
-}
-
-// the worker whose range holds page `page`
-__device__ __forceinline__ int worker_of_page(long long page, long long total, int workers)
-{
-    long long w = (page * workers) / total;
-    while (worker_begin(w + 1, total, workers) <= page) ++w;
-    while (worker_begin(w, total, workers) > page) --w;
-    return (int)w;
-}
-
-// Merge of the partials of query row `rh` (fixed segment order), MAXC >= nseg.
-template <int MAXC>
-__device__ __forceinline__ void combine_rows(const AttnParams &p, int b_row0, int rows, int group, int kvh, int nseg, int lane)
-{
-    // half a wavefront per query row, four head dims per lane; all loads of a pass are
-    // issued before the first is used
-    constexpr int ROWS_PER_PASS = 2 * (16 / MAXC);
-    const int half = lane >> 5, l32 = lane & 31;
-    for (int r0 = 0; r0 < rows; r0 += ROWS_PER_PASS) {
-        unsigned long long mlv[16], a0[16], a1[16];
-        size_t rh_of[16 / MAXC];
-        bool rv_of[16 / MAXC];
-#pragma unroll
-        for (int j = 0; j < 16 / MAXC; ++j) {
-            const int r = r0 + 2 * j + half;
-            const bool rv = r < rows;
-            const int rr = rv ? r : 0;
-            const size_t rh = (size_t)(b_row0 + rr / group) * p.Hq + kvh * group + rr % group;
-            rh_of[j] = rh;
-            rv_of[j] = rv;
-            const size_t base = rh * p.max_chunks;
-            const unsigned long long *ml = reinterpret_cast<const unsigned long long *>(p.ws_ml) + base;
-            const unsigned long long *pa =
-                reinterpret_cast<const unsigned long long *>(p.ws_acc) + base * (kD / 2) + 2 * l32;
-#pragma unroll
-            for (int c = 0; c < MAXC; ++c) {
-                const bool on = rv && c < nseg;
-                mlv[j * MAXC + c] = on ? fetch_u64(ml + c) : pack_f32x2(kEmptyMax, 0.0f);
-                a0[j * MAXC + c] = on ? fetch_u64(pa + (size_t)c * (kD / 2)) : 0ull;
-                a1[j * MAXC + c] = on ? fetch_u64(pa + (size_t)c * (kD / 2) + 1) : 0ull;
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < 16 / MAXC; ++j) {
-            float mx = kEmptyMax;
-#pragma unroll
-            for (int c = 0; c < MAXC; ++c) mx = fmaxf(mx, __uint_as_float((uint32_t)mlv[j * MAXC + c]));
-            float denom = 0.0f;
-            f32x4 o = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-            for (int c = 0; c < MAXC; ++c) {
-                const unsigned long long mlw = mlv[j * MAXC + c];
-                const float w = fast_exp2(__uint_as_float((uint32_t)mlw) - mx);
-                denom = fmaf(w, __uint_as_float((uint32_t)(mlw >> 32)), denom);
-                o[0] = fmaf(w, __uint_as_float((uint32_t)a0[j * MAXC + c]), o[0]);
-                o[1] = fmaf(w, __uint_as_float((uint32_t)(a0[j * MAXC + c] >> 32)), o[1]);
-                o[2] = fmaf(w, __uint_as_float((uint32_t)a1[j * MAXC + c]), o[2]);
-                o[3] = fmaf(w, __uint_as_float((uint32_t)(a1[j * MAXC + c] >> 32)), o[3]);
-            }
-            if (rv_of[j]) *reinterpret_cast<f32x4 *>(p.out + rh_of[j] * kD + 4 * l32) = o * (1.0f / denom);
-        }
-    }
-}
-
 template <int NT, bool SPLIT_P>
-__device__ void attn_role(const AttnParams &p, int block, AttnShared &sh)
+__device__ void attn_role(const AttnParams &p, int item, AttnShared<NT> &sh)
 {
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63;
     const int n16 = lane & 15;
     const int g = lane >> 4;
+    const int chunk = item % p.max_chunks;
+    const int unit = item / p.max_chunks;
+    const int kvh = unit % p.Hkv;
+    const int b = unit / p.Hkv;
 
-    // ---- page counts of all requests, prefix-summed once per block
-    {
-        const int per = (p.B + kThreads - 1) / kThreads;
-        const int b0 = tid * per;
-        int mine = 0;
-        for (int i = 0; i < per; ++i) {
-            const int bb = b0 + i;
-            if (bb < p.B) mine += (p.kv_len[bb] + SPEC_BLOCK_SIZE - 1) / SPEC_BLOCK_SIZE;
-        }
-        int incl = mine;
-#pragma unroll
-        for (int o = 1; o < kWave; o <<= 1) {
-            const int up = __shfl_up(incl, o);
-            if (lane >= o) incl += up;
-        }
-        if (lane == kWave - 1) sh.wave_total[wave] = incl;
-        __syncthreads();
-        int offset = 0;
-        for (int w = 0; w < wave; ++w) offset += sh.wave_total[w];
-        int run = offset + incl - mine;   // exclusive prefix of this thread's first request
-        for (int i = 0; i < per; ++i) {
-            const int bb = b0 + i;
-            if (bb < p.B) {
-                sh.cum_pages[bb] = run;
-                run += (p.kv_len[bb] + SPEC_BLOCK_SIZE - 1) / SPEC_BLOCK_SIZE;
-            }
-        }
-        if (tid == kThreads - 1) sh.cum_pages[p.B] = offset + incl;
-        __syncthreads();
-    }
-    const long long total_pages = (long long)sh.cum_pages[p.B] * p.Hkv;
-    const int worker = block * kWaves + wave;
-    if (worker >= p.workers) return;
-    const long long range_begin = worker_begin(worker, total_pages, p.workers);
-    const long long range_end = worker_begin(worker + 1, total_pages, p.workers);
-
+    // When no request is split, a wavefront's block-table entries do not depend on kv_len:
+    // fetch them alongside it (entries past the request's pages are never used).
+    int bt = 0;
+    if (p.max_chunks == 1 && wave + kWaves * lane < p.max_blocks_per_req)
+        bt = p.block_table[(size_t)b * p.max_blocks_per_req + wave + kWaves * lane];
+    const int L = p.kv_len[b];
+    const int nchunks = (L + p.chunk_tokens - 1) / p.chunk_tokens;
+    if (chunk >= nchunks) return;
+    // even chunks per request, page aligned (never longer than chunk_tokens)
+    const int C = ((L + nchunks - 1) / nchunks + SPEC_BLOCK_SIZE - 1) & ~(SPEC_BLOCK_SIZE - 1);
+    const int row0 = p.cu_q_len[b];
+    const int q_len = p.cu_q_len[b + 1] - row0;
     const int group = p.Hq / p.Hkv;
+    const int rows = q_len * group;
+    const int tok0 = chunk * C;
+    const int tok1 = min(L, tok0 + C);
+    const int npages = (tok1 - tok0 + SPEC_BLOCK_SIZE - 1) / SPEC_BLOCK_SIZE;  // <= 256
+    const int page0 = tok0 / SPEC_BLOCK_SIZE;
+
+    // block-table entries of this wavefront's pages (wave, wave+4, ...), one per lane
+    if (p.max_chunks != 1 && wave + kWaves * lane < npages)
+        bt = p.block_table[(size_t)b * p.max_blocks_per_req + page0 + wave + kWaves * lane];
+
+    // Q as the B operand of S^T = K Q^T, and each lane's last visible key
+    bf16x8 qreg[NT][4];
+    int limit[NT];
+    int out_row[NT];   // packed (token row * Hq + head) of this lane's query row, -1 if padding
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int r = nt * 16 + n16;
+        const bool valid = r < rows;
+        const int j = valid ? r / group : 0;
+        const int gq = valid ? r % group : 0;
+        const size_t rh = (size_t)(row0 + j) * p.Hq + kvh * group + gq;
+        const __bf16 *qp = static_cast<const __bf16 *>(p.q) + rh * kD + g * 8;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+            qreg[nt][kk] = valid ? *reinterpret_cast<const bf16x8 *>(qp + kk * 32) : z;
+        }
+        limit[nt] = valid ? L - q_len + j : -1;
+        out_row[nt] = valid ? (int)rh : -1;
+    }
+
+    // Pages are read with buffer loads through a descriptor that covers exactly one
+    // (page, KV head): 4 KB of K or V.  A page index past the end gets a descriptor of
+    // length 0, for which the hardware returns zeros without touching memory.  That
+    // keeps every load unconditional, so the loads of later pages stay in flight across
+    // the arithmetic of the current one (a branch around them would make the compiler
+    // wait for all outstanding loads at every use).
+    const char *khead = static_cast<const char *>(p.k_cache) + (size_t)kvh * kPageHeadBytes;
+    const char *vhead = static_cast<const char *>(p.v_cache) + (size_t)kvh * kPageHeadBytes;
     const size_t page_stride = (size_t)p.Hkv * kPageHeadBytes;
+    const int my_pages = npages > wave ? (npages - wave + kWaves - 1) / kWaves : 0;   // pages wave, wave+4, ...
     const int lane_off = lane * 16;
 
-    for (long long pos = range_begin; pos < range_end;) {
-        // ---- locate the segment: request b, KV head kvh, pages [lp, lp + seg_pages) of it
-        int lo = 0, hi = p.B - 1;
-        while (lo < hi) {   // largest b with cum_pages[b] * Hkv <= pos
-            const int mid = (lo + hi + 1) >> 1;
-            if ((long long)sh.cum_pages[mid] * p.Hkv <= pos) lo = mid; else hi = mid - 1;
-        }
-        const int b = lo;
-        const int n_b = sh.cum_pages[b + 1] - sh.cum_pages[b];
-        const long long unit0 = (long long)sh.cum_pages[b] * p.Hkv;
-        const int kvh = (int)((pos - unit0) / n_b);
-        const long long unit_begin = unit0 + (long long)kvh * n_b;
-        const int lp = (int)(pos - unit_begin);
-        const int seg_pages = (int)min((long long)(n_b - lp), range_end - pos);
-        pos += seg_pages;
+    auto load_page = [&](int it, PageRegs &r) {   // it-th page of this wavefront
+        const bool valid = it < my_pages;
+        const int page = __builtin_amdgcn_readlane(bt, valid ? it : 0);
+        const int bytes = valid ? kPageHeadBytes : 0;
+        const __amdgpu_buffer_rsrc_t kd = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<char *>(khead + (size_t)page * page_stride), 0, bytes, kBufferFlags);
+        const __amdgpu_buffer_rsrc_t vd = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<char *>(vhead + (size_t)page * page_stride), 0, bytes, kBufferFlags);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) r.k[i] = __builtin_amdgcn_raw_buffer_load_b128(kd, lane_off, i * 1024, 0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) r.v[i] = __builtin_amdgcn_raw_buffer_load_b128(vd, lane_off, i * 1024, 0);
+    };
 
-        const int L = p.kv_len[b];
-        const int row0 = p.cu_q_len[b];
-        const int q_len = p.cu_q_len[b + 1] - row0;
-        const int rows = q_len * group;
-        const int first_masked_token = L - q_len + 1;   // keys from here on are hidden from some row (or past the end)
+    f32x4 acc[NT][8];
+    float m_run[NT], l_run[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        m_run[nt] = kEmptyMax;
+        l_run[nt] = 0.0f;
+#pragma unroll
+        for (int mt = 0; mt < 8; ++mt) acc[nt][mt] = (f32x4){0.0f, 0.0f, 0.0f, 0.0f};
+    }
 
-        // Q as the B operand of S^T = K Q^T, and each lane's last visible key
-        bf16x8 qreg[NT][4];
-        int limit[NT];
-        int out_row[NT];   // packed (token row * Hq + head) of this lane's query row, -1 if padding
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            const int r = nt * 16 + n16;
-            const bool valid = r < rows;
-            const int j = valid ? r / group : 0;
-            const int gq = valid ? r % group : 0;
-            const size_t rh = (size_t)(row0 + j) * p.Hq + kvh * group + gq;
-            const __bf16 *qp = static_cast<const __bf16 *>(p.q) + rh * kD + g * 8;
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-                qreg[nt][kk] = valid ? *reinterpret_cast<const bf16x8 *>(qp + kk * 32) : z;
-            }
-            limit[nt] = valid ? L - q_len + j : -1;
-            out_row[nt] = valid ? (int)rh : -1;
-        }
+    const int first_masked_token = L - q_len + 1;  // keys from here on are hidden from some row (or past the end)
 
-        f32x4 acc[NT][8];
-        float m_run[NT], l_run[NT];
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            m_run[nt] = kEmptyMax;
-            l_run[nt] = 0.0f;
-#pragma unroll
-            for (int mt = 0; mt < 8; ++mt) acc[nt][mt] = (f32x4){0.0f, 0.0f, 0.0f, 0.0f};
-        }
+    // Software pipeline: the loads of the next DEPTH pages are in flight while a page is
+    // consumed.  The ring is indexed statically (the loop is unrolled by its length).
+    auto consume = [&](PageRegs &cur, int pi) {
+        const int page_tok = tok0 + pi * SPEC_BLOCK_SIZE;
+        const bool need_mask = page_tok + SPEC_BLOCK_SIZE > first_masked_token;
+        const int tbase = page_tok + 4 * g;
 
-        const char *khead = static_cast<const char *>(p.k_cache) + (size_t)kvh * kPageHeadBytes;
-        const char *vhead = static_cast<const char *>(p.v_cache) + (size_t)kvh * kPageHeadBytes;
-
-        // ---- the segment, in windows of 64 pages (one block-table entry per lane)
-        for (int w0 = 0; w0 < seg_pages; w0 += kWave) {
-            const int win_pages = min(kWave, seg_pages - w0);
-            const int win_first = lp + w0;
-            int bt = 0;
-            if (lane < win_pages) bt = p.block_table[(size_t)b * p.max_blocks_per_req + win_first + lane];
-
-            // Pages are read with buffer loads through a descriptor that covers exactly one
-            // (page, KV head): 4 KB of K or V.  A page index past the end gets a descriptor of
-            // length 0, for which the hardware returns zeros without touching memory.  That
-            // keeps every load unconditional (a branch around the loads would make the
-            // compiler wait for all outstanding loads at every use).
-            auto load_page = [&](int it, PageRegs &r) {   // it-th page of the window
-                const bool valid = it < win_pages;
-                const int page = __builtin_amdgcn_readlane(bt, valid ? it : 0);
-                const int bytes = valid ? kPageHeadBytes : 0;
-                const __amdgpu_buffer_rsrc_t kd = __builtin_amdgcn_make_buffer_rsrc(
-                    const_cast<char *>(khead + (size_t)page * page_stride), 0, bytes, kBufferFlags);
-                const __amdgpu_buffer_rsrc_t vd = __builtin_amdgcn_make_buffer_rsrc(
-                    const_cast<char *>(vhead + (size_t)page * page_stride), 0, bytes, kBufferFlags);
+        {
+            // slots past kv_len in the request's last page may hold anything: clear their V
+            // (done on every page, without a branch, so that no load has to be waited for early)
+            const int nvalid = min(max(L - tbase, 0), 4);
+            const uint32_t lo = nvalid >= 2 ? 0xFFFFFFFFu : (nvalid == 1 ? 0x0000FFFFu : 0u);
+            const uint32_t hi = nvalid >= 4 ? 0xFFFFFFFFu : (nvalid == 3 ? 0x0000FFFFu : 0u);
 #pragma unroll
-                for (int i = 0; i < 4; ++i) r.k[i] = __builtin_amdgcn_raw_buffer_load_b128(kd, lane_off, i * 1024, 0);
-#pragma unroll
-                for (int i = 0; i < 4; ++i) r.v[i] = __builtin_amdgcn_raw_buffer_load_b128(vd, lane_off, i * 1024, 0);
-            };
-
-            auto consume = [&](PageRegs &cur, int page_index) {
-                const int page_tok = page_index * SPEC_BLOCK_SIZE;
-                const bool need_mask = page_tok + SPEC_BLOCK_SIZE > first_masked_token;
-                const int tbase = page_tok + 4 * g;
-                {
-                    // slots past kv_len in the request's last page may hold anything: clear their V
-                    // (on every page, without a branch, so that no load has to be waited for early)
-                    const int nvalid = min(max(L - tbase, 0), 4);
-                    const uint32_t lo32 = nvalid >= 2 ? 0xFFFFFFFFu : (nvalid == 1 ? 0x0000FFFFu : 0u);
-                    const uint32_t hi32 = nvalid >= 4 ? 0xFFFFFFFFu : (nvalid == 3 ? 0x0000FFFFu : 0u);
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        cur.v[i].x &= lo32; cur.v[i].y &= hi32;
-                        cur.v[i].z &= lo32; cur.v[i].w &= hi32;
-                    }
-                }
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    f32x4 s = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-                    for (int kk = 0; kk < 4; ++kk)
-                        s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, cur.k[kk]), qreg[nt][kk], s, 0, 0, 0);
-                    s *= p.scale_log2;
-                    if (need_mask) {
-#pragma unroll
-                        for (int r = 0; r < 4; ++r)
-                            if (tbase + r > limit[nt]) s[r] = -INFINITY;
-                    }
-                    float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
-                    mx = fmaxf(mx, __shfl_xor(mx, 16));
-                    mx = fmaxf(mx, __shfl_xor(mx, 32));
-                    const float m_new = fmaxf(m_run[nt], mx);
-                    const float alpha = fast_exp2(m_run[nt] - m_new);
-                    f32x4 pr;
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) pr[r] = fast_exp2(s[r] - m_new);
-                    l_run[nt] = l_run[nt] * alpha + ((pr[0] + pr[1]) + (pr[2] + pr[3]));
-                    m_run[nt] = m_new;
-                    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
-#pragma unroll
-                        for (int mt = 0; mt < 8; ++mt) acc[nt][mt] *= alpha;
-                    }
-                    const bf16x4 p_hi = __builtin_convertvector(pr, bf16x4);
-                    bf16x4 p_lo;
-                    if (SPLIT_P) p_lo = __builtin_convertvector(pr - __builtin_convertvector(p_hi, f32x4), bf16x4);
-#pragma unroll
-                    for (int mt = 0; mt < 8; ++mt) {
-                        const u32x4 vv = cur.v[mt >> 1];
-                        const u32x2 half = (mt & 1) ? (u32x2){vv.z, vv.w} : (u32x2){vv.x, vv.y};
-                        const bf16x4 va = __builtin_bit_cast(bf16x4, half);
-                        acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va, p_hi, acc[nt][mt], 0, 0, 0);
-                        if (SPLIT_P) acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va, p_lo, acc[nt][mt], 0, 0, 0);
-                    }
-                }
-            };
-
-            // Two register sets.  While one page is consumed the next page's loads are in
-            // flight.  Order inside a half-step: wait for the page about to be consumed (at
-            // that point it is the only one outstanding, so the full wait the compiler emits
-            // waits for nothing else), then issue the other page's loads, then the arithmetic.
-            auto arrived = [&](PageRegs &r) {
-                asm volatile("" ::"v"(r.k[0]), "v"(r.k[1]), "v"(r.k[2]), "v"(r.k[3]), "v"(r.v[0]), "v"(r.v[1]),
-                             "v"(r.v[2]), "v"(r.v[3])
-                             : "memory");
-            };
-            PageRegs page_a, page_b;
-            load_page(0, page_a);
-            for (int it0 = 0; it0 < win_pages; it0 += 2) {
-                arrived(page_a);
-                load_page(it0 + 1, page_b);
-                consume(page_a, win_first + it0);
-                arrived(page_b);
-                load_page(it0 + 2, page_a);
-                if (it0 + 1 < win_pages) consume(page_b, win_first + it0 + 1);
+            for (int i = 0; i < 4; ++i) {
+                cur.v[i].x &= lo; cur.v[i].y &= hi;
+                cur.v[i].z &= lo; cur.v[i].w &= hi;
             }
         }
 
-        // each lane summed its own four tokens per page: finish the row sums
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-            l_run[nt] += __shfl_xor(l_run[nt], 16);
-            l_run[nt] += __shfl_xor(l_run[nt], 32);
-        }
-
-        if (lp == 0 && seg_pages == n_b) {
-            // the whole (request, KV head) was this segment: normalise and write the output
+            f32x4 s = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                if (out_row[nt] < 0) continue;
-                const float inv = 1.0f / l_run[nt];
-                float *dst = p.out + (size_t)out_row[nt] * kD + 4 * g;
+            for (int kk = 0; kk < 4; ++kk)
+                s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, cur.k[kk]), qreg[nt][kk], s, 0, 0, 0);
+            s *= p.scale_log2;
+            if (need_mask) {
 #pragma unroll
-                for (int mt = 0; mt < 8; ++mt) *reinterpret_cast<f32x4 *>(dst + 16 * mt) = acc[nt][mt] * inv;
+                for (int r = 0; r < 4; ++r)
+                    if (tbase + r > limit[nt]) s[r] = -INFINITY;
             }
-            continue;
+            float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
+            mx = fmaxf(mx, __shfl_xor(mx, 16));
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float m_new = fmaxf(m_run[nt], mx);
+            const float alpha = fast_exp2(m_run[nt] - m_new);
+            f32x4 pr;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) pr[r] = fast_exp2(s[r] - m_new);
+            l_run[nt] = l_run[nt] * alpha + ((pr[0] + pr[1]) + (pr[2] + pr[3]));
+            m_run[nt] = m_new;
+            if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+                for (int mt = 0; mt < 8; ++mt) acc[nt][mt] *= alpha;
+            }
+            const bf16x4 p_hi = __builtin_convertvector(pr, bf16x4);
+            bf16x4 p_lo;
+            if (SPLIT_P) p_lo = __builtin_convertvector(pr - __builtin_convertvector(p_hi, f32x4), bf16x4);
+#pragma unroll
+            for (int mt = 0; mt < 8; ++mt) {
+                const u32x4 vv = cur.v[mt >> 1];
+                const u32x2 half = (mt & 1) ? (u32x2){vv.z, vv.w} : (u32x2){vv.x, vv.y};
+                const bf16x4 va = __builtin_bit_cast(bf16x4, half);
+                acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va, p_hi, acc[nt][mt], 0, 0, 0);
+                if (SPLIT_P) acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va, p_lo, acc[nt][mt], 0, 0, 0);
+            }
         }
+    };
 
-        // one partial per query row in the slot of this segment: acc[dim], running max, running sum
-        const int first_worker = worker_of_page(unit_begin, total_pages, p.workers);
-        const int nseg = worker_of_page(unit_begin + n_b - 1, total_pages, p.workers) - first_worker + 1;
-        const int seg_index = worker - first_worker;
-        if (seg_index >= p.max_chunks) continue;   // cannot happen when the host lengths match the device's
+    // Two register batches of P pages each.  While one batch is consumed the loads of the
+    // other are in flight.  The order inside a half-step matters: first wait for the batch
+    // about to be consumed (at that point it is the only one outstanding, so the full
+    // wait the compiler emits waits for nothing else), then issue the other batch's loads,
+    // then do the arithmetic, which needs no further wait.
+    constexpr int P = 1;   // pages per batch: two bring nothing once the launch keeps the memory system busy
+    PageRegs batch_a[P], batch_b[P];
+    auto load_batch = [&](int it, PageRegs(&r)[P]) {
+#pragma unroll
+        for (int j = 0; j < P; ++j) load_page(it + j, r[j]);
+    };
+    auto arrived = [&](PageRegs(&r)[P]) {
+#pragma unroll
+        for (int j = 0; j < P; ++j)
+            asm volatile("" ::"v"(r[j].k[0]), "v"(r[j].k[1]), "v"(r[j].k[2]), "v"(r[j].k[3]), "v"(r[j].v[0]),
+                         "v"(r[j].v[1]), "v"(r[j].v[2]), "v"(r[j].v[3])
+                         : "memory");
+    };
+    auto consume_batch = [&](PageRegs(&r)[P], int it) {
+#pragma unroll
+        for (int j = 0; j < P; ++j)
+            if (it + j < my_pages) consume(r[j], wave + kWaves * (it + j));
+    };
+    load_batch(0, batch_a);
+    for (int it0 = 0; it0 < my_pages; it0 += 2 * P) {
+        arrived(batch_a);
+        load_batch(it0 + P, batch_b);
+        consume_batch(batch_a, it0);
+        arrived(batch_b);
+        load_batch(it0 + 2 * P, batch_a);
+        consume_batch(batch_b, it0 + P);
+    }
+
+    // each lane summed its own four tokens per page: finish the row sums
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        l_run[nt] += __shfl_xor(l_run[nt], 16);
+        l_run[nt] += __shfl_xor(l_run[nt], 32);
+    }
+
+    // merge the four wavefronts: 2,3 -> 0,1 then 1 -> 0
+    auto put = [&](int buf) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+#pragma unroll
+            for (int mt = 0; mt < 8; ++mt) sh.acc[buf][nt][mt][lane] = acc[nt][mt];
+            sh.m[buf][nt][lane] = m_run[nt];
+            sh.l[buf][nt][lane] = l_run[nt];
+        }
+    };
+    auto merge = [&](int buf) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const float mo = sh.m[buf][nt][lane];
+            const float lo = sh.l[buf][nt][lane];
+            const float mn = fmaxf(m_run[nt], mo);
+            const float wa = fast_exp2(m_run[nt] - mn);
+            const float wb = fast_exp2(mo - mn);
+            l_run[nt] = l_run[nt] * wa + lo * wb;
+            m_run[nt] = mn;
+#pragma unroll
+            for (int mt = 0; mt < 8; ++mt) acc[nt][mt] = acc[nt][mt] * wa + sh.acc[buf][nt][mt][lane] * wb;
+        }
+    };
+    if (wave >= 2) put(wave - 2);
+    __syncthreads();
+    if (wave < 2) merge(wave);
+    __syncthreads();
+    if (wave == 1) put(0);
+    __syncthreads();
+
+    if (nchunks == 1) {
+        // the only chunk of this (request, KV head): normalise and write the output
+        if (wave != 0) return;
+        merge(0);
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
             if (out_row[nt] < 0) continue;
-            const size_t slot = (size_t)out_row[nt] * p.max_chunks + seg_index;
+            const float inv = 1.0f / l_run[nt];
+            float *dst = p.out + (size_t)out_row[nt] * kD + 4 * g;
+#pragma unroll
+            for (int mt = 0; mt < 8; ++mt) *reinterpret_cast<f32x4 *>(dst + 16 * mt) = acc[nt][mt] * inv;
+        }
+        return;
+    }
+
+    if (wave == 0) {
+        merge(0);
+        // one partial per query row: acc[dim], running max, running sum
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            if (out_row[nt] < 0) continue;
+            const size_t slot = (size_t)out_row[nt] * p.max_chunks + chunk;
             unsigned long long *dst = reinterpret_cast<unsigned long long *>(p.ws_acc + slot * kD + 4 * g);
 #pragma unroll
             for (int mt = 0; mt < 8; ++mt) {
@@ -940,59 +873,112 @@ __device__ void attn_role(const AttnParams &p, int block, AttnShared &sh)
             if (g == 0)
                 publish_u64(reinterpret_cast<unsigned long long *>(p.ws_ml + slot * 2), pack_f32x2(m_run[nt], l_run[nt]));
         }
-        if (!p.fused_combine) continue;   // a separate combine launch merges the partials
+        if (!p.fused_combine) return;   // a separate combine launch merges the partials
         writes_complete();  // the partial is in memory before the ticket is taken
-        int last = 0;
         if (lane == 0) {
-            unsigned long long *ticket = &p.tickets[(size_t)b * p.Hkv + kvh];
+            unsigned long long *ticket = &p.tickets[unit];
             const uint32_t before = ticket_arrive(ticket, p.generation);
-            last = (before + 1u == (uint32_t)nseg) ? 1 : 0;
+            const int last = (before + 1u == (uint32_t)nchunks) ? 1 : 0;
             if (last) ticket_reset(ticket);
+            sh.last = last;
         }
-        last = __builtin_amdgcn_readfirstlane(last);
-        if (!last) continue;
-        order_after_ticket();
-        // last segment of this (request, KV head) to arrive: merge all segments in order
-        if (nseg <= 2) combine_rows<2>(p, row0, rows, group, kvh, nseg, lane);
-        else if (nseg <= 4) combine_rows<4>(p, row0, rows, group, kvh, nseg, lane);
-        else if (nseg <= 8) combine_rows<8>(p, row0, rows, group, kvh, nseg, lane);
-        else combine_rows<16>(p, row0, rows, group, kvh, nseg, lane);
+    }
+    if (!p.fused_combine) return;
+    __syncthreads();
+    if (!sh.last) return;
+    order_after_ticket();
+
+    // Last chunk of this (request, KV head) to finish: merge all chunks in chunk order.
+    // Half a wavefront takes a query row (four head dims per lane); every load of a
+    // pass is issued before the first is used, so a pass costs one memory round trip.
+    constexpr int MAXC = 16;   // the plan guarantees nchunks <= MAXC on this path
+    const int half = lane >> 5, l32 = lane & 31;
+    for (int r0 = 2 * wave; r0 < rows; r0 += 2 * kWaves) {
+        const int r = r0 + half;
+        const bool rv = r < rows;
+        const int rr = rv ? r : 0;
+        const size_t rh = (size_t)(row0 + rr / group) * p.Hq + kvh * group + rr % group;
+        const size_t base = rh * p.max_chunks;
+        const unsigned long long *ml = reinterpret_cast<const unsigned long long *>(p.ws_ml) + base;
+        const unsigned long long *pa =
+            reinterpret_cast<const unsigned long long *>(p.ws_acc) + base * (kD / 2) + 2 * l32;
+        unsigned long long mlv[MAXC], a0[MAXC], a1[MAXC];
+#pragma unroll
+        for (int c = 0; c < MAXC; ++c) {
+            const bool on = rv && c < nchunks;
+            mlv[c] = on ? fetch_u64(ml + c) : pack_f32x2(kEmptyMax, 0.0f);
+            a0[c] = on ? fetch_u64(pa + (size_t)c * (kD / 2)) : 0ull;
+            a1[c] = on ? fetch_u64(pa + (size_t)c * (kD / 2) + 1) : 0ull;
+        }
+        float mx = kEmptyMax;
+#pragma unroll
+        for (int c = 0; c < MAXC; ++c) mx = fmaxf(mx, __uint_as_float((uint32_t)mlv[c]));
+        float denom = 0.0f;
+        f32x4 o = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int c = 0; c < MAXC; ++c) {
+            const float w = fast_exp2(__uint_as_float((uint32_t)mlv[c]) - mx);
+            denom = fmaf(w, __uint_as_float((uint32_t)(mlv[c] >> 32)), denom);
+            o[0] = fmaf(w, __uint_as_float((uint32_t)a0[c]), o[0]);
+            o[1] = fmaf(w, __uint_as_float((uint32_t)(a0[c] >> 32)), o[1]);
+            o[2] = fmaf(w, __uint_as_float((uint32_t)a1[c]), o[2]);
+            o[3] = fmaf(w, __uint_as_float((uint32_t)(a1[c] >> 32)), o[3]);
+        }
+        if (rv) *reinterpret_cast<f32x4 *>(p.out + rh * kD + 4 * l32) = o * (1.0f / denom);
     }
 }
 
 // ===========================================================================
 // The kernel
 // ===========================================================================
-// Grid order: the attention blocks come first, one per compute unit, so that the
-// hardware dispatcher hands each compute unit exactly one of them; the rejection
-// items (statistics, then race, then final) follow and run in the slot that is left
-// on each compute unit, underneath the attention stream.
+// Grid order.  The rejection items always keep their own order (statistics, race, final).
+//  - Few, long attention blocks (no more than fit on the device at once): attention
+//    first.  The hardware dispatcher then spreads them evenly over the compute units
+//    (two of them on one unit would take twice as long as the rest), and the
+//    rejection items fill the block slots that are left.
+//  - Many attention blocks: the rejection items are spread evenly among them, so that
+//    at any time only a fraction of the resident blocks belongs to the latency-bound
+//    rejection stages and the rest keep streaming the KV cache.  Position i holds an
+//    attention item iff floor((i+1) * n_attn / n) > floor(i * n_attn / n).
 struct GridSplit {
-    int n_attn_blocks, n_stat;
+    int n_stat, n_reject, n_attn;
+    int attn_first;
 };
 
 template <int NT, bool HAS_ATTN, bool HAS_REJECT, bool SPLIT_P>
 __global__ __launch_bounds__(kThreads, 2) void spec_step_kernel(AttnParams ap, RejectParams rp, GridSplit gs)
 {
     int item = blockIdx.x;
-    if constexpr (HAS_ATTN) {
-        if (item < gs.n_attn_blocks) {
-            __shared__ AttnShared ash;
-            attn_role<NT, SPLIT_P>(ap, item, ash);
-            return;
+    bool is_attn = HAS_ATTN;
+    if constexpr (HAS_ATTN && HAS_REJECT) {
+        if (gs.attn_first) {
+            is_attn = item < gs.n_attn;
+            if (!is_attn) item -= gs.n_attn;
+        } else {
+            const long long n = (long long)gs.n_reject + gs.n_attn;
+            const int before = (int)(((long long)item * gs.n_attn) / n);
+            const int upto = (int)(((long long)(item + 1) * gs.n_attn) / n);
+            is_attn = upto > before;
+            item = is_attn ? before : item - before;
         }
-        item -= gs.n_attn_blocks;
     }
     if constexpr (HAS_REJECT) {
-        __shared__ RejectShared rsh;
-        if (item < gs.n_stat) {
-            stats_role(rp, item, rsh);
-        } else {
-            const int after = item - gs.n_stat;
-            const int n_race = rp.B * rp.race_segments;
-            if (after < n_race) race_role(rp, after, rsh);
-            else final_role(rp, after - n_race, rsh);
+        if (!is_attn) {
+            __shared__ RejectShared rsh;
+            if (item < gs.n_stat) {
+                stats_role(rp, item, rsh);
+            } else {
+                const int after = item - gs.n_stat;
+                const int n_race = rp.B * rp.race_segments;
+                if (after < n_race) race_role(rp, after, rsh);
+                else final_role(rp, after - n_race, rsh);
+            }
+            return;
         }
+    }
+    if constexpr (HAS_ATTN) {
+        __shared__ AttnShared<NT> ash;
+        attn_role<NT, SPLIT_P>(ap, item, ash);
     }
 }
 
@@ -1000,9 +986,11 @@ template <int NT, bool HAS_ATTN, bool HAS_REJECT>
 hipError_t launch(const AttnParams &ap, const RejectParams &rp, int n_stat, int n_attn, int n_race, hipStream_t stream)
 {
     GridSplit gs;
-    gs.n_attn_blocks = n_attn;
     gs.n_stat = n_stat;
-    const dim3 grid(n_attn + n_stat + n_race);
+    gs.n_reject = n_stat + n_race;
+    gs.n_attn = n_attn;
+    gs.attn_first = (n_attn <= ap.attn_first_limit) ? 1 : 0;
+    const dim3 grid(n_stat + n_race + n_attn);
     if (HAS_ATTN && !ap.split_p)
         hipLaunchKernelGGL((spec_step_kernel<NT, HAS_ATTN, HAS_REJECT, false>), grid, dim3(kThreads), 0, stream, ap, rp, gs);
     else
@@ -1010,58 +998,7 @@ hipError_t launch(const AttnParams &ap, const RejectParams &rp, int n_stat, int 
     return hipGetLastError();
 }
 
-// Merge of the segment partials by a separate launch (used when a (request, KV head)
-// can be spread over more segments than the in-place merge takes).  grid = T*Hq blocks of
-// 128 threads, one head dim per thread.
-__global__ __launch_bounds__(kD) void attn_combine_segments_kernel(AttnParams p)
-{
-    const int row = blockIdx.x / p.Hq;
-    const int h = blockIdx.x % p.Hq;
-    const int tid = threadIdx.x;
-    const int b = request_of_target_row(p.cu_q_len, p.B, row);
-    const int kvh = h / (p.Hq / p.Hkv);
-    // pages before request b, and in all requests
-    __shared__ int sh_before[kD], sh_all[kD];
-    int before = 0, all = 0;
-    for (int bb = tid; bb < p.B; bb += kD) {
-        const int n = (p.kv_len[bb] + SPEC_BLOCK_SIZE - 1) / SPEC_BLOCK_SIZE;
-        all += n;
-        if (bb < b) before += n;
-    }
-    sh_before[tid] = before;
-    sh_all[tid] = all;
-    __syncthreads();
-    for (int o = kD / 2; o > 0; o >>= 1) {
-        if (tid < o) { sh_before[tid] += sh_before[tid + o]; sh_all[tid] += sh_all[tid + o]; }
-        __syncthreads();
-    }
-    const long long total_pages = (long long)sh_all[0] * p.Hkv;
-    const int n_b = (p.kv_len[b] + SPEC_BLOCK_SIZE - 1) / SPEC_BLOCK_SIZE;
-    const long long unit_begin = (long long)sh_before[0] * p.Hkv + (long long)kvh * n_b;
-    const int first_worker = worker_of_page(unit_begin, total_pages, p.workers);
-    const int nseg = worker_of_page(unit_begin + n_b - 1, total_pages, p.workers) - first_worker + 1;
-    if (nseg == 1) return;   // written straight to the output by the attention kernel
-    const size_t base = ((size_t)row * p.Hq + h) * p.max_chunks;
-    float mx = kEmptyMax;
-#pragma unroll 8
-    for (int c = 0; c < nseg; ++c) mx = fmaxf(mx, p.ws_ml[(base + c) * 2]);
-    float denom = 0.0f, acc = 0.0f;
-#pragma unroll 8
-    for (int c = 0; c < nseg; ++c) {
-        const float w = fast_exp2(p.ws_ml[(base + c) * 2] - mx);
-        denom = fmaf(w, p.ws_ml[(base + c) * 2 + 1], denom);
-        acc = fmaf(w, p.ws_acc[(base + c) * kD + tid], acc);
-    }
-    p.out[((size_t)row * p.Hq + h) * kD + tid] = acc / denom;
-}
-
 }  // namespace
-
-hipError_t launch_attn_combine_segments(const AttnParams &p, hipStream_t stream)
-{
-    hipLaunchKernelGGL(attn_combine_segments_kernel, dim3(p.T * p.Hq), dim3(kD), 0, stream, p);
-    return hipGetLastError();
-}
 
 hipError_t launch_step_fused(const AttnParams *attn, int row_tiles, const RejectParams *reject, hipStream_t stream)
 {
@@ -1077,10 +1014,10 @@ hipError_t launch_step_fused(const AttnParams *attn, int row_tiles, const Reject
     }
     if (attn != nullptr) {
         ap = *attn;
-        if (ap.d != kD || row_tiles < 1 || row_tiles > 3 || (ap.fused_combine && ap.max_chunks > 16) ||
-            ap.B > kMaxScanRequests || ap.workers < 1)
+        if (ap.d != kD || ap.chunk_tokens > 4096 || ap.chunk_tokens % SPEC_BLOCK_SIZE != 0 || row_tiles < 1 ||
+            row_tiles > 3 || (ap.fused_combine && ap.max_chunks > 16))
             return hipErrorInvalidValue;
-        n_attn = (ap.workers + kWaves - 1) / kWaves;
+        n_attn = ap.B * ap.Hkv * ap.max_chunks;
     }
     if (attn == nullptr) return launch<1, false, true>(ap, rp, n_stat, 0, n_race, stream);
     if (reject == nullptr) {
