@@ -168,9 +168,10 @@ __device__ __forceinline__ uint4 philox4x32_10(uint4 c, uint32_t k0, uint32_t k1
 {
 #pragma unroll
     for (int r = 0; r < 10; ++r) {
-        const uint32_t hi_a = __umulhi(0xD2511F53u, c.x), lo_a = 0xD2511F53u * c.x;
-        const uint32_t hi_b = __umulhi(0xCD9E8D57u, c.z), lo_b = 0xCD9E8D57u * c.z;
-        c = make_uint4(hi_b ^ c.y ^ k0, lo_b, hi_a ^ c.w ^ k1, lo_a);
+        // full 64-bit products: one multiply instruction each instead of a high and a low one
+        const unsigned long long pa = (unsigned long long)0xD2511F53u * (unsigned long long)c.x;
+        const unsigned long long pb = (unsigned long long)0xCD9E8D57u * (unsigned long long)c.z;
+        c = make_uint4((uint32_t)(pb >> 32) ^ c.y ^ k0, (uint32_t)pb, (uint32_t)(pa >> 32) ^ c.w ^ k1, (uint32_t)pa);
         k0 += 0x9E3779B9u;
         k1 += 0xBB67AE85u;
     }
@@ -200,7 +201,7 @@ struct RejectShared {
 // fp32 hi/lo pair inside fused multiply-adds).
 __device__ __forceinline__ void stats_block(const RejectParams &p, int row, int seg, RejectShared &sh)
 {
-    constexpr int UNROLL = 8;   // 128 bytes per thread in flight
+    constexpr int UNROLL = 16;   // 256 bytes per thread in flight (these blocks share the attention role's register budget)
     const int tid = threadIdx.x;
     const float *base = row < p.T ? p.target_logits + (size_t)row * p.V
                                   : p.draft_logits + (size_t)(row - p.T) * p.V;
@@ -450,10 +451,24 @@ __device__ bool accept_phase(const RejectParams &p, int b, RejectShared &sh, boo
     return true;
 }
 
+// Statistics items are ordered by request (its target rows, then its draft rows), so that
+// the first requests' statistics are complete early and their races can start while
+// later requests' rows are still being read.
 __device__ void stats_role(const RejectParams &p, int item, RejectShared &sh)
 {
-    const int row = item / p.stat_segments;
-    stats_block(p, row, item - row * p.stat_segments, sh);
+    const int rec = item / p.stat_segments;          // (request, row of the request)
+    const int seg = item - rec * p.stat_segments;
+    int lo = 0, hi = p.B - 1;
+    while (lo < hi) {   // largest b with 2 * cu_q_len[b] - b <= rec  (rows of the requests before b)
+        const int mid = (lo + hi + 1) >> 1;
+        if (2 * p.cu_q_len[mid] - mid <= rec) lo = mid; else hi = mid - 1;
+    }
+    const int b = lo;
+    const int row_t0 = p.cu_q_len[b];
+    const int k = p.cu_q_len[b + 1] - row_t0 - 1;
+    const int ri = rec - (2 * row_t0 - b);
+    const int row = ri <= k ? row_t0 + ri : p.T + (row_t0 - b) + (ri - k - 1);
+    stats_block(p, row, seg, sh);
 }
 
 // Offsets of the race rows of request b after accept_phase.
@@ -938,8 +953,13 @@ __device__ void attn_role(const AttnParams &p, int item, AttnShared<NT> &sh)
 //    rejection items fill the block slots that are left.
 //  - Many attention blocks: the rejection items are spread evenly among them, so that
 //    at any time only a fraction of the resident blocks belongs to the latency-bound
-//    rejection stages and the rest keep streaming the KV cache.  Position i holds an
-//    attention item iff floor((i+1) * n_attn / n) > floor(i * n_attn / n).
+//    rejection stages and the rest keep streaming the KV cache.  The mixing is done per
+//    row of 8 consecutive blocks: the hardware deals consecutive blocks to the 8 XCDs in
+//    turn, and a finer pattern would alias with that (with equal counts, "every other
+//    block" would put all attention on four XCDs and all rejection on the other four).
+//    Row r is an attention row iff floor((r+1) * rows_attn / rows) > floor(r * rows_attn / rows).
+constexpr int kXcds = 8;
+
 struct GridSplit {
     int n_stat, n_reject, n_attn;
     int attn_first;
@@ -955,11 +975,16 @@ __global__ __launch_bounds__(kThreads, 2) void spec_step_kernel(AttnParams ap, R
             is_attn = item < gs.n_attn;
             if (!is_attn) item -= gs.n_attn;
         } else {
-            const long long n = (long long)gs.n_reject + gs.n_attn;
-            const int before = (int)(((long long)item * gs.n_attn) / n);
-            const int upto = (int)(((long long)(item + 1) * gs.n_attn) / n);
+            // rows of kXcds consecutive blocks (one per XCD, the hardware deals blocks to the
+            // XCDs round-robin) share a role, so every XCD sees the same mix
+            const int row = item / kXcds, col = item % kXcds;
+            const long long rows_attn = (gs.n_attn + kXcds - 1) / kXcds;
+            const long long rows_all = rows_attn + (gs.n_reject + kXcds - 1) / kXcds;
+            const int before = (int)((row * rows_attn) / rows_all);
+            const int upto = (int)(((row + 1) * rows_attn) / rows_all);
             is_attn = upto > before;
-            item = is_attn ? before : item - before;
+            item = (is_attn ? before : row - before) * kXcds + col;
+            if (item >= (is_attn ? gs.n_attn : gs.n_reject)) return;   // padding of the last row
         }
     }
     if constexpr (HAS_REJECT) {
@@ -990,7 +1015,9 @@ hipError_t launch(const AttnParams &ap, const RejectParams &rp, int n_stat, int 
     gs.n_reject = n_stat + n_race;
     gs.n_attn = n_attn;
     gs.attn_first = (n_attn <= ap.attn_first_limit) ? 1 : 0;
-    const dim3 grid(n_stat + n_race + n_attn);
+    const int n_reject = n_stat + n_race;
+    const bool mixed = HAS_ATTN && HAS_REJECT && !gs.attn_first;
+    const dim3 grid(mixed ? ((n_attn + kXcds - 1) / kXcds + (n_reject + kXcds - 1) / kXcds) * kXcds : n_reject + n_attn);
     if (HAS_ATTN && !ap.split_p)
         hipLaunchKernelGGL((spec_step_kernel<NT, HAS_ATTN, HAS_REJECT, false>), grid, dim3(kThreads), 0, stream, ap, rp, gs);
     else
