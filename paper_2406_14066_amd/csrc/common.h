@@ -52,6 +52,7 @@ struct AttnParams {
     uint32_t generation;  // tags this call's ticket values, never 0
     int32_t fused_combine;        // matrix kernel: the last chunk's block merges the partials (needs max_chunks <= 16)
     int32_t attn_first_limit;     // attention blocks go first in the grid when there are at most this many
+    float reject_span;            // fraction of the attention items among which the rejection items are spread in the grid
     int32_t split_p;              // feed the softmax weights to the PV product as bf16 high + low parts
     int32_t single_chunk_direct;  // requests with one chunk were written straight to `out`: the combine kernel skips them
 };
@@ -90,9 +91,18 @@ struct RejectParams {
     uint32_t generation;
 };
 
+// Order in which the attention items take the requests (longest first), passed as a
+// kernel argument.  n == 0: the given order.
+constexpr int kMaxOrdered = 1024;
+struct UnitOrder {
+    int32_t n;
+    alignas(4) uint16_t request[kMaxOrdered];
+};
+
 // One launch for the whole step (either half may be absent).  `attn` needs the
-// matrix-instruction path (bf16, SPEC_KV_MFMA, d = 128, row_tiles <= 3).
-hipError_t launch_step_fused(const AttnParams *attn, int row_tiles, const RejectParams *reject, hipStream_t stream);
+// matrix-instruction path (bf16, SPEC_KV_MFMA, d = 128, row_tiles <= 3).  `order` may be null.
+hipError_t launch_step_fused(const AttnParams *attn, int row_tiles, const RejectParams *reject, const UnitOrder *order,
+                             hipStream_t stream);
 
 // Generic attention path: partial kernel + combine kernel.
 hipError_t launch_attn_generic(const AttnParams &p, int dtype, hipStream_t stream);

@@ -6,6 +6,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <algorithm>
 #include <atomic>
 #include <vector>
 
@@ -231,6 +232,11 @@ AttnParams attn_params(const spec_attn_args *a, const AttnPlan &pl, char *ws)
     p.fused_combine = pl.fused_combine;
     p.single_chunk_direct = pl.use_mfma;
     p.split_p = 1;
+    p.reject_span = 0.5f;
+    if (const char *e = getenv("SPEC_VERIFY_REJECT_SPAN")) {   // tuning switch
+        const double v = strtod(e, nullptr);
+        if (v > 0.0 && v <= 1.0) p.reject_span = (float)v;
+    }
     p.attn_first_limit = 2 * compute_units();   // two blocks fit on a compute unit
     if (const char *e = getenv("SPEC_VERIFY_SPLIT_P")) p.split_p = (e[0] != '0');   // experiment switch
     return p;
@@ -258,6 +264,27 @@ RejectParams reject_params(const spec_reject_args *r, const RejectPlan &pl, char
     p.race_info = p.race_partial + (size_t)r->B * pl.race_segments * 2;
     p.generation = next_generation();
     return p;
+}
+
+// Requests by falling KV length (stable; from the host copy of kv_len).  The grid takes the
+// attention items in this order: blocks that run at the same time then take about
+// equally long, which the in-order hardware dispatcher needs to keep its block slots
+// filled, and the short items even out the end of the launch.  Returns null (given order)
+// when all lengths are equal or there are too many requests for the table.
+const UnitOrder *make_order(const spec_attn_args *a, UnitOrder &order)
+{
+    order.n = 0;
+    if (a->B > kMaxOrdered) return nullptr;
+    bool equal = true;
+    for (int b = 1; b < a->B; ++b)
+        if (a->host_kv_len[b] != a->host_kv_len[0]) equal = false;
+    if (equal) return nullptr;
+    std::vector<int> idx(a->B);
+    for (int b = 0; b < a->B; ++b) idx[b] = b;
+    std::stable_sort(idx.begin(), idx.end(), [&](int x, int y) { return a->host_kv_len[x] > a->host_kv_len[y]; });
+    for (int b = 0; b < a->B; ++b) order.request[b] = (uint16_t)idx[b];
+    order.n = a->B;
+    return &order;
 }
 
 spec_status run_attn_generic(const AttnParams &p, int dtype, hipStream_t stream)
@@ -304,8 +331,10 @@ spec_status spec_verify_attn(const spec_attn_args *attn, void *workspace, size_t
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const AttnParams ap = attn_params(attn, pl, static_cast<char *>(workspace));
     if (!pl.use_mfma) return run_attn_generic(ap, attn->qkv_dtype, stream);
-    hipError_t err =
-        timed(SPEC_KERNEL_ATTN, stream, [&] { return launch_step_fused(&ap, pl.row_tiles, nullptr, stream); });
+    UnitOrder order_table;
+    const UnitOrder *order = make_order(attn, order_table);
+    hipError_t err = timed(SPEC_KERNEL_ATTN, stream,
+                           [&] { return launch_step_fused(&ap, pl.row_tiles, nullptr, order, stream); });
     if (err == hipSuccess && !pl.fused_combine && pl.max_chunks > 1)
         err = timed(SPEC_KERNEL_ATTN_COMBINE, stream, [&] { return launch_attn_combine(ap, stream); });
     return err == hipSuccess ? SPEC_OK : SPEC_EHIP;
@@ -322,7 +351,7 @@ spec_status spec_reject_sample(const spec_reject_args *reject, void *workspace, 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const RejectParams rp = reject_params(reject, pl, static_cast<char *>(workspace));
     const hipError_t err =
-        timed(SPEC_KERNEL_REJECT, stream, [&] { return launch_step_fused(nullptr, 0, &rp, stream); });
+        timed(SPEC_KERNEL_REJECT, stream, [&] { return launch_step_fused(nullptr, 0, &rp, nullptr, stream); });
     return err == hipSuccess ? SPEC_OK : SPEC_EHIP;
 }
 
@@ -343,8 +372,10 @@ spec_status spec_verify_step(const spec_attn_args *attn, const spec_reject_args 
     const RejectParams rp = reject_params(reject, rpl, static_cast<char *>(workspace));
     if (apl.use_mfma) {
         // the whole step in one launch
-        hipError_t err =
-            timed(SPEC_KERNEL_STEP, stream, [&] { return launch_step_fused(&ap, apl.row_tiles, &rp, stream); });
+        UnitOrder order_table;
+        const UnitOrder *order = make_order(attn, order_table);
+        hipError_t err = timed(SPEC_KERNEL_STEP, stream,
+                               [&] { return launch_step_fused(&ap, apl.row_tiles, &rp, order, stream); });
         if (err == hipSuccess && !apl.fused_combine && apl.max_chunks > 1)
             err = timed(SPEC_KERNEL_ATTN_COMBINE, stream, [&] { return launch_attn_combine(ap, stream); });
         return err == hipSuccess ? SPEC_OK : SPEC_EHIP;
@@ -352,7 +383,7 @@ spec_status spec_verify_step(const spec_attn_args *attn, const spec_reject_args 
     st = run_attn_generic(ap, attn->qkv_dtype, stream);
     if (st != SPEC_OK) return st;
     const hipError_t err =
-        timed(SPEC_KERNEL_REJECT, stream, [&] { return launch_step_fused(nullptr, 0, &rp, stream); });
+        timed(SPEC_KERNEL_REJECT, stream, [&] { return launch_step_fused(nullptr, 0, &rp, nullptr, stream); });
     return err == hipSuccess ? SPEC_OK : SPEC_EHIP;
 }
 

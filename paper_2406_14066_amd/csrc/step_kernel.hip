@@ -49,6 +49,8 @@
 
 #include <float.h>
 #include <math.h>
+#include <stddef.h>
+#include <string.h>
 
 namespace specv {
 
@@ -631,8 +633,18 @@ struct AttnShared {
     int last;
 };
 
+// The order in which the attention items take the requests (longest first), as the kernel
+// sees it: a pointer into the kernel-argument segment, read with scalar loads (taking the
+// address of the by-value argument instead would make the compiler copy the table to
+// private memory).  Two 16-bit entries per word; n == 0: the given order.
+typedef const uint32_t __attribute__((address_space(4))) *uniform_u32_ptr;
+struct OrderTable {
+    int n;
+    uniform_u32_ptr pairs;
+};
+
 template <int NT, bool SPLIT_P>
-__device__ void attn_role(const AttnParams &p, int item, AttnShared<NT> &sh)
+__device__ void attn_role(const AttnParams &p, OrderTable order, int item, AttnShared<NT> &sh)
 {
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -640,9 +652,13 @@ __device__ void attn_role(const AttnParams &p, int item, AttnShared<NT> &sh)
     const int n16 = lane & 15;
     const int g = lane >> 4;
     const int chunk = item % p.max_chunks;
-    const int unit = item / p.max_chunks;
-    const int kvh = unit % p.Hkv;
-    const int b = unit / p.Hkv;
+    const int kvh = (item / p.max_chunks) % p.Hkv;
+    int b = item / p.max_chunks / p.Hkv;   // rank in the order of the attention items
+    if (order.n > 0) {
+        const uint32_t pair = order.pairs[b >> 1];
+        b = (int)((b & 1) ? pair >> 16 : pair & 0xFFFFu);
+    }
+    const int unit = b * p.Hkv + kvh;
 
     // When no request is split, a wavefront's block-table entries do not depend on kv_len:
     // fetch them alongside it (entries past the request's pages are never used).
@@ -963,11 +979,24 @@ constexpr int kXcds = 8;
 struct GridSplit {
     int n_stat, n_reject, n_attn;
     int attn_first;
+    int rows_attn_mixed;   // attention rows among which the rejection rows are spread; the other attention rows follow
+};
+
+// All kernel arguments in one struct, so that the place of the order table inside the
+// kernel-argument segment is known.
+struct StepArgs {
+    AttnParams ap;
+    RejectParams rp;
+    GridSplit gs;
+    UnitOrder order;
 };
 
 template <int NT, bool HAS_ATTN, bool HAS_REJECT, bool SPLIT_P>
-__global__ __launch_bounds__(kThreads, 2) void spec_step_kernel(AttnParams ap, RejectParams rp, GridSplit gs)
+__global__ __launch_bounds__(kThreads, 2) void spec_step_kernel(StepArgs args)
 {
+    const AttnParams &ap = args.ap;
+    const RejectParams &rp = args.rp;
+    const GridSplit &gs = args.gs;
     int item = blockIdx.x;
     bool is_attn = HAS_ATTN;
     if constexpr (HAS_ATTN && HAS_REJECT) {
@@ -978,12 +1007,17 @@ __global__ __launch_bounds__(kThreads, 2) void spec_step_kernel(AttnParams ap, R
             // rows of kXcds consecutive blocks (one per XCD, the hardware deals blocks to the
             // XCDs round-robin) share a role, so every XCD sees the same mix
             const int row = item / kXcds, col = item % kXcds;
-            const long long rows_attn = (gs.n_attn + kXcds - 1) / kXcds;
+            const long long rows_attn = gs.rows_attn_mixed;
             const long long rows_all = rows_attn + (gs.n_reject + kXcds - 1) / kXcds;
-            const int before = (int)((row * rows_attn) / rows_all);
-            const int upto = (int)(((row + 1) * rows_attn) / rows_all);
-            is_attn = upto > before;
-            item = (is_attn ? before : row - before) * kXcds + col;
+            if (row < rows_all) {
+                const int before = (int)((row * rows_attn) / rows_all);
+                const int upto = (int)(((row + 1) * rows_attn) / rows_all);
+                is_attn = upto > before;
+                item = (is_attn ? before : row - before) * kXcds + col;
+            } else {   // the attention rows after the last rejection row
+                is_attn = true;
+                item = (int)(rows_attn + (row - rows_all)) * kXcds + col;
+            }
             if (item >= (is_attn ? gs.n_attn : gs.n_reject)) return;   // padding of the last row
         }
     }
@@ -1003,31 +1037,51 @@ __global__ __launch_bounds__(kThreads, 2) void spec_step_kernel(AttnParams ap, R
     }
     if constexpr (HAS_ATTN) {
         __shared__ AttnShared<NT> ash;
-        attn_role<NT, SPLIT_P>(ap, item, ash);
+        OrderTable order;
+        order.n = args.order.n;
+        order.pairs = (uniform_u32_ptr)((const char __attribute__((address_space(4))) *)__builtin_amdgcn_kernarg_segment_ptr() +
+                                        offsetof(StepArgs, order) + offsetof(UnitOrder, request));
+        attn_role<NT, SPLIT_P>(ap, order, item, ash);
     }
 }
 
 template <int NT, bool HAS_ATTN, bool HAS_REJECT>
-hipError_t launch(const AttnParams &ap, const RejectParams &rp, int n_stat, int n_attn, int n_race, hipStream_t stream)
+hipError_t launch(const AttnParams &ap, const RejectParams &rp, int n_stat, int n_attn, int n_race,
+                  const UnitOrder *order, hipStream_t stream)
 {
-    GridSplit gs;
+    StepArgs args;
+    args.ap = ap;
+    args.rp = rp;
+    args.order.n = 0;
+    if (HAS_ATTN && order != nullptr && order->n > 0) {
+        args.order.n = order->n;
+        memcpy(args.order.request, order->request, sizeof(uint16_t) * (size_t)order->n);
+    }
+    GridSplit &gs = args.gs;
     gs.n_stat = n_stat;
     gs.n_reject = n_stat + n_race;
     gs.n_attn = n_attn;
     gs.attn_first = (n_attn <= ap.attn_first_limit) ? 1 : 0;
     const int n_reject = n_stat + n_race;
     const bool mixed = HAS_ATTN && HAS_REJECT && !gs.attn_first;
+    // The rejection stages of a request wait for each other, so the last rejection item sits
+    // well before the end of the grid: the tail of the launch is attention only.
+    const int rows_attn_all = (n_attn + kXcds - 1) / kXcds;
+    gs.rows_attn_mixed = (int)(rows_attn_all * (double)ap.reject_span);
+    if (gs.rows_attn_mixed < 1) gs.rows_attn_mixed = 1;
+    if (gs.rows_attn_mixed > rows_attn_all) gs.rows_attn_mixed = rows_attn_all;
     const dim3 grid(mixed ? ((n_attn + kXcds - 1) / kXcds + (n_reject + kXcds - 1) / kXcds) * kXcds : n_reject + n_attn);
     if (HAS_ATTN && !ap.split_p)
-        hipLaunchKernelGGL((spec_step_kernel<NT, HAS_ATTN, HAS_REJECT, false>), grid, dim3(kThreads), 0, stream, ap, rp, gs);
+        hipLaunchKernelGGL((spec_step_kernel<NT, HAS_ATTN, HAS_REJECT, false>), grid, dim3(kThreads), 0, stream, args);
     else
-        hipLaunchKernelGGL((spec_step_kernel<NT, HAS_ATTN, HAS_REJECT, true>), grid, dim3(kThreads), 0, stream, ap, rp, gs);
+        hipLaunchKernelGGL((spec_step_kernel<NT, HAS_ATTN, HAS_REJECT, true>), grid, dim3(kThreads), 0, stream, args);
     return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_step_fused(const AttnParams *attn, int row_tiles, const RejectParams *reject, hipStream_t stream)
+hipError_t launch_step_fused(const AttnParams *attn, int row_tiles, const RejectParams *reject, const UnitOrder *order,
+                              hipStream_t stream)
 {
     AttnParams ap = {};
     RejectParams rp = {};
@@ -1042,22 +1096,22 @@ hipError_t launch_step_fused(const AttnParams *attn, int row_tiles, const Reject
     if (attn != nullptr) {
         ap = *attn;
         if (ap.d != kD || ap.chunk_tokens > 4096 || ap.chunk_tokens % SPEC_BLOCK_SIZE != 0 || row_tiles < 1 ||
-            row_tiles > 3 || (ap.fused_combine && ap.max_chunks > 16))
+            row_tiles > 3 || (ap.fused_combine && ap.max_chunks > 16) || (order != nullptr && order->n != 0 && order->n != ap.B))
             return hipErrorInvalidValue;
         n_attn = ap.B * ap.Hkv * ap.max_chunks;
     }
-    if (attn == nullptr) return launch<1, false, true>(ap, rp, n_stat, 0, n_race, stream);
+    if (attn == nullptr) return launch<1, false, true>(ap, rp, n_stat, 0, n_race, nullptr, stream);
     if (reject == nullptr) {
         switch (row_tiles) {
-            case 1: return launch<1, true, false>(ap, rp, 0, n_attn, 0, stream);
-            case 2: return launch<2, true, false>(ap, rp, 0, n_attn, 0, stream);
-            default: return launch<3, true, false>(ap, rp, 0, n_attn, 0, stream);
+            case 1: return launch<1, true, false>(ap, rp, 0, n_attn, 0, order, stream);
+            case 2: return launch<2, true, false>(ap, rp, 0, n_attn, 0, order, stream);
+            default: return launch<3, true, false>(ap, rp, 0, n_attn, 0, order, stream);
         }
     }
     switch (row_tiles) {
-        case 1: return launch<1, true, true>(ap, rp, n_stat, n_attn, n_race, stream);
-        case 2: return launch<2, true, true>(ap, rp, n_stat, n_attn, n_race, stream);
-        default: return launch<3, true, true>(ap, rp, n_stat, n_attn, n_race, stream);
+        case 1: return launch<1, true, true>(ap, rp, n_stat, n_attn, n_race, order, stream);
+        case 2: return launch<2, true, true>(ap, rp, n_stat, n_attn, n_race, order, stream);
+        default: return launch<3, true, true>(ap, rp, n_stat, n_attn, n_race, order, stream);
     }
 }
 
