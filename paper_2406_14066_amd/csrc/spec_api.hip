@@ -132,8 +132,10 @@ AttnPlan plan_attn(const spec_attn_args *a)
     if (pl.use_mfma) {
         // One block per (request, KV head, chunk).  Splitting costs (partials, a merge, more
         // block start-ups), so the longest request is split only as far as needed to give every
-        // compute unit a block.
-        long target_blocks = compute_units();
+        // compute unit a block; two blocks with three row tiles, whose wavefronts spend a
+        // larger share of their time on arithmetic and need a second one beside them to keep
+        // loads in flight.
+        long target_blocks = (long)compute_units() * (pl.row_tiles >= 3 ? 2 : 1);
         if (const char *t = getenv("SPEC_VERIFY_TARGET_BLOCKS")) {   // tuning switch
             const long v = strtol(t, nullptr, 10);
             if (v >= 1 && v <= (1 << 20)) target_blocks = v;

@@ -297,7 +297,7 @@ __device__ void race_segment(const RejectParams &p, const float *target_row, con
     int best_id = 0x7FFFFFFF;
     const int g_begin = v0 >> 2, g_end = v1 >> 2;
     const uint32_t c3 = (p.step_hi24 << 8) | 1u;
-    constexpr int U = 2;  // row vectors in flight per thread
+    constexpr int U = 8;  // row vectors in flight per thread
     for (int g0 = g_begin + threadIdx.x; g0 < g_end; g0 += kThreads * U) {
         float4 xt[U], xd[U];
 #pragma unroll
@@ -460,11 +460,14 @@ __device__ void stats_role(const RejectParams &p, int item, RejectShared &sh)
 {
     const int rec = item / p.stat_segments;          // (request, row of the request)
     const int seg = item - rec * p.stat_segments;
-    int lo = 0, hi = p.B - 1;
-    while (lo < hi) {   // largest b with 2 * cu_q_len[b] - b <= rec  (rows of the requests before b)
-        const int mid = (lo + hi + 1) >> 1;
-        if (2 * p.cu_q_len[mid] - mid <= rec) lo = mid; else hi = mid - 1;
-    }
+    // largest b with 2 * cu_q_len[b] - b <= rec (rows of the requests before b).  Start from
+    // where b would be if all requests had equally many rows, and walk: with equal draft
+    // lengths that is one round of loads instead of the log2(B) dependent ones of a bisection.
+    const int nrec = 2 * p.T - p.B;
+    int lo = (int)(((long long)rec * p.B) / nrec);
+    if (lo > p.B - 1) lo = p.B - 1;
+    while (lo > 0 && 2 * p.cu_q_len[lo] - lo > rec) --lo;
+    while (lo < p.B - 1 && 2 * p.cu_q_len[lo + 1] - (lo + 1) <= rec) ++lo;
     const int b = lo;
     const int row_t0 = p.cu_q_len[b];
     const int k = p.cu_q_len[b + 1] - row_t0 - 1;
