@@ -25,6 +25,8 @@ constexpr float kEmptyMax = -1.0e30f;  // running maximum of a row that has seen
 //   ml   [T*Hq][max_chunks][2]  running maximum m (base-2 units) and sum l of 2^(s_t - m)
 // tickets [B*Hkv] count the chunks of a (request, KV head) that have finished;
 // the block that finishes last merges the partials (matrix-instruction kernel).
+constexpr int kMaxFusedChunks = 64;   // beyond this many chunks per request a separate launch merges the partials
+
 struct AttnPlan {
     int32_t chunk_tokens;
     int32_t max_chunks;
@@ -50,7 +52,7 @@ struct AttnParams {
     float *ws_ml;
     unsigned long long *tickets;
     uint32_t generation;  // tags this call's ticket values, never 0
-    int32_t fused_combine;        // matrix kernel: the last chunk's block merges the partials (needs max_chunks <= 16)
+    int32_t fused_combine;        // matrix kernel: the last chunk's block merges the partials (needs max_chunks <= kMaxFusedChunks)
     int32_t attn_first_limit;     // attention blocks go first in the grid when there are at most this many
     float reject_span;            // fraction of the attention items among which the rejection items are spread in the grid
     int32_t split_p;              // feed the softmax weights to the PV product as bf16 high + low parts

@@ -156,7 +156,7 @@ AttnPlan plan_attn(const spec_attn_args *a)
         pl.chunk_tokens = 256;  // one key per thread of the generic kernel
     }
     pl.max_chunks = (max_len + pl.chunk_tokens - 1) / pl.chunk_tokens;
-    pl.fused_combine = (pl.use_mfma && pl.max_chunks <= 16) ? 1 : 0;
+    pl.fused_combine = (pl.use_mfma && pl.max_chunks <= kMaxFusedChunks) ? 1 : 0;
     const size_t slots = (size_t)a->T * a->Hq * pl.max_chunks;
     pl.acc_bytes = align_up(slots * a->d * sizeof(float));
     pl.ml_bytes = align_up(slots * 2 * sizeof(float));
@@ -239,7 +239,7 @@ AttnParams attn_params(const spec_attn_args *a, const AttnPlan &pl, char *ws)
         const double v = strtod(e, nullptr);
         if (v > 0.0 && v <= 1.0) p.reject_span = (float)v;
     }
-    p.attn_first_limit = 2 * compute_units();   // two blocks fit on a compute unit
+    p.attn_first_limit = compute_units();   // one attention block per compute unit leaves a slot beside it for the rejection items
     if (const char *e = getenv("SPEC_VERIFY_SPLIT_P")) p.split_p = (e[0] != '0');   // experiment switch
     return p;
 }

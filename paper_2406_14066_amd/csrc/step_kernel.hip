@@ -925,7 +925,7 @@ __device__ void attn_role(const AttnParams &p, OrderTable order, int item, AttnS
     // Last chunk of this (request, KV head) to finish: merge all chunks in chunk order.
     // Half a wavefront takes a query row (four head dims per lane); every load of a
     // pass is issued before the first is used, so a pass costs one memory round trip.
-    constexpr int MAXC = 16;   // the plan guarantees nchunks <= MAXC on this path
+    constexpr int GROUP = 8;   // chunks merged per pass
     const int half = lane >> 5, l32 = lane & 31;
     for (int r0 = 2 * wave; r0 < rows; r0 += 2 * kWaves) {
         const int r = r0 + half;
@@ -936,27 +936,33 @@ __device__ void attn_role(const AttnParams &p, OrderTable order, int item, AttnS
         const unsigned long long *ml = reinterpret_cast<const unsigned long long *>(p.ws_ml) + base;
         const unsigned long long *pa =
             reinterpret_cast<const unsigned long long *>(p.ws_acc) + base * (kD / 2) + 2 * l32;
-        unsigned long long mlv[MAXC], a0[MAXC], a1[MAXC];
-#pragma unroll
-        for (int c = 0; c < MAXC; ++c) {
-            const bool on = rv && c < nchunks;
-            mlv[c] = on ? fetch_u64(ml + c) : pack_f32x2(kEmptyMax, 0.0f);
-            a0[c] = on ? fetch_u64(pa + (size_t)c * (kD / 2)) : 0ull;
-            a1[c] = on ? fetch_u64(pa + (size_t)c * (kD / 2) + 1) : 0ull;
-        }
-        float mx = kEmptyMax;
-#pragma unroll
-        for (int c = 0; c < MAXC; ++c) mx = fmaxf(mx, __uint_as_float((uint32_t)mlv[c]));
-        float denom = 0.0f;
+        float mx = kEmptyMax, denom = 0.0f;
         f32x4 o = {0.0f, 0.0f, 0.0f, 0.0f};
+        for (int c0 = 0; c0 < nchunks; c0 += GROUP) {
+            unsigned long long mlv[GROUP], a0[GROUP], a1[GROUP];
 #pragma unroll
-        for (int c = 0; c < MAXC; ++c) {
-            const float w = fast_exp2(__uint_as_float((uint32_t)mlv[c]) - mx);
-            denom = fmaf(w, __uint_as_float((uint32_t)(mlv[c] >> 32)), denom);
-            o[0] = fmaf(w, __uint_as_float((uint32_t)a0[c]), o[0]);
-            o[1] = fmaf(w, __uint_as_float((uint32_t)(a0[c] >> 32)), o[1]);
-            o[2] = fmaf(w, __uint_as_float((uint32_t)a1[c]), o[2]);
-            o[3] = fmaf(w, __uint_as_float((uint32_t)(a1[c] >> 32)), o[3]);
+            for (int c = 0; c < GROUP; ++c) {
+                const bool on = rv && c0 + c < nchunks;
+                mlv[c] = on ? fetch_u64(ml + c0 + c) : pack_f32x2(kEmptyMax, 0.0f);
+                a0[c] = on ? fetch_u64(pa + (size_t)(c0 + c) * (kD / 2)) : 0ull;
+                a1[c] = on ? fetch_u64(pa + (size_t)(c0 + c) * (kD / 2) + 1) : 0ull;
+            }
+            float gmx = mx;
+#pragma unroll
+            for (int c = 0; c < GROUP; ++c) gmx = fmaxf(gmx, __uint_as_float((uint32_t)mlv[c]));
+            const float keep = fast_exp2(mx - gmx);   // rescale of what earlier passes summed
+            denom *= keep;
+            o *= keep;
+            mx = gmx;
+#pragma unroll
+            for (int c = 0; c < GROUP; ++c) {
+                const float w = fast_exp2(__uint_as_float((uint32_t)mlv[c]) - mx);
+                denom = fmaf(w, __uint_as_float((uint32_t)(mlv[c] >> 32)), denom);
+                o[0] = fmaf(w, __uint_as_float((uint32_t)a0[c]), o[0]);
+                o[1] = fmaf(w, __uint_as_float((uint32_t)(a0[c] >> 32)), o[1]);
+                o[2] = fmaf(w, __uint_as_float((uint32_t)a1[c]), o[2]);
+                o[3] = fmaf(w, __uint_as_float((uint32_t)(a1[c] >> 32)), o[3]);
+            }
         }
         if (rv) *reinterpret_cast<f32x4 *>(p.out + rh * kD + 4 * l32) = o * (1.0f / denom);
     }
@@ -1099,7 +1105,7 @@ hipError_t launch_step_fused(const AttnParams *attn, int row_tiles, const Reject
     if (attn != nullptr) {
         ap = *attn;
         if (ap.d != kD || ap.chunk_tokens > 4096 || ap.chunk_tokens % SPEC_BLOCK_SIZE != 0 || row_tiles < 1 ||
-            row_tiles > 3 || (ap.fused_combine && ap.max_chunks > 16) || (order != nullptr && order->n != 0 && order->n != ap.B))
+            row_tiles > 3 || (ap.fused_combine && ap.max_chunks > kMaxFusedChunks) || (order != nullptr && order->n != 0 && order->n != ap.B))
             return hipErrorInvalidValue;
         n_attn = ap.B * ap.Hkv * ap.max_chunks;
     }
