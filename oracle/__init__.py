@@ -59,6 +59,11 @@ def _load():
             [c.c_int32, c.c_int32] + [c.c_void_p] * 4 + [c.c_uint64, c.c_uint64] + [c.c_void_p] * 7
         )
         lib.oracle_reject_sample.restype = c.c_int
+        lib.oracle_reject_greedy.argtypes = [c.c_int32, c.c_int32] + [c.c_void_p] * 7
+        lib.oracle_reject_greedy.restype = c.c_int
+        lib.oracle_reject_onehot.argtypes = (
+            [c.c_int32, c.c_int32] + [c.c_void_p] * 3 + [c.c_uint64, c.c_uint64] + [c.c_void_p] * 7)
+        lib.oracle_reject_onehot.restype = c.c_int
         lib.oracle_expected_generated_len.argtypes = [c.c_double, c.c_int32]
         lib.oracle_expected_generated_len.restype = c.c_double
         _lib = lib
@@ -173,4 +178,48 @@ def reject_sample(target_logits, draft_logits, draft_tokens, cu_q_len, seed, ste
         _ptr(acc), _ptr(nxt), _ptr(out_tokens), _ptr(cnt), _ptr(dec_u), _ptr(dec_ratio), _ptr(margin))
     if rc != 0:
         raise ValueError("oracle_reject_sample: malformed arguments")
+    return RejectResult(acc, nxt, out_tokens, cnt, dec_u[: T - B], dec_ratio[: T - B], margin)
+
+
+def reject_greedy(target_logits, draft_tokens, cu_q_len, counters=None):
+    """Greedy acceptance; no random numbers.  dec_u / dec_ratio / race_margin of the result are empty."""
+    t = _carr(target_logits, np.float32)
+    cu = _carr(cu_q_len, np.int32)
+    B = cu.shape[0] - 1
+    T, V = t.shape
+    assert int(cu[-1]) == T
+    x = _carr(draft_tokens, np.int32)
+    assert x.shape == (T - B,)
+    acc = np.zeros(B, dtype=np.int32)
+    nxt = np.zeros(B, dtype=np.int32)
+    out_tokens = np.zeros((B, K_MAX + 1), dtype=np.int32)
+    cnt = np.zeros(8, dtype=np.int64) if counters is None else _carr(counters, np.int64).copy()
+    rc = _load().oracle_reject_greedy(B, V, _ptr(t), _ptr(x), _ptr(cu), _ptr(acc), _ptr(nxt), _ptr(out_tokens), _ptr(cnt))
+    if rc != 0:
+        raise ValueError("oracle_reject_greedy: malformed arguments")
+    empty = np.zeros(0, dtype=np.float64)
+    return RejectResult(acc, nxt, out_tokens, cnt, empty, empty, np.full(B, np.inf))
+
+
+def reject_onehot(target_logits, draft_tokens, cu_q_len, seed, step, counters=None):
+    """Stochastic acceptance against a point-mass draft distribution (proposer without logits)."""
+    t = _carr(target_logits, np.float32)
+    cu = _carr(cu_q_len, np.int32)
+    B = cu.shape[0] - 1
+    T, V = t.shape
+    assert int(cu[-1]) == T
+    x = _carr(draft_tokens, np.int32)
+    assert x.shape == (T - B,)
+    acc = np.zeros(B, dtype=np.int32)
+    nxt = np.zeros(B, dtype=np.int32)
+    out_tokens = np.zeros((B, K_MAX + 1), dtype=np.int32)
+    cnt = np.zeros(8, dtype=np.int64) if counters is None else _carr(counters, np.int64).copy()
+    dec_u = np.full(max(T - B, 1), np.nan, dtype=np.float64)
+    dec_ratio = np.full(max(T - B, 1), np.nan, dtype=np.float64)
+    margin = np.zeros(B, dtype=np.float64)
+    rc = _load().oracle_reject_onehot(
+        B, V, _ptr(t), _ptr(x), _ptr(cu), int(seed), int(step),
+        _ptr(acc), _ptr(nxt), _ptr(out_tokens), _ptr(cnt), _ptr(dec_u), _ptr(dec_ratio), _ptr(margin))
+    if rc != 0:
+        raise ValueError("oracle_reject_onehot: malformed arguments")
     return RejectResult(acc, nxt, out_tokens, cnt, dec_u[: T - B], dec_ratio[: T - B], margin)

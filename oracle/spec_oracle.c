@@ -357,6 +357,151 @@ int oracle_reject_sample(int32_t B, int32_t V, const float *target_logits,
     return 0;
 }
 
+/* ------------------------------------------------------------------ */
+/* Greedy acceptance (Section 2.2, "Speculative Decoding": a greedy      */
+/* sampling method keeps draft token i iff it is the token that         */
+/* maximises the target distribution of its position, accepts the       */
+/* leading run of such tokens, and takes the next token from the target  */
+/* distribution that follows the last accepted one; with greedy          */
+/* sampling that is its most likely token).  No random numbers, no       */
+/* draft logits.  Equal maxima: the lowest token id is "the" maximiser.  */
+/* The arg-max is taken on the raw fp32 logits (softmax is monotone).    */
+/* counters as in oracle_reject_sample (near ties: none, slot 4 += 0).   */
+/* ------------------------------------------------------------------ */
+int oracle_reject_greedy(int32_t B, int32_t V, const float *target_logits,
+                         const int32_t *draft_tokens, const int32_t *cu_q_len,
+                         int32_t *accepted_len, int32_t *next_token, int32_t *out_tokens,
+                         int64_t *counters)
+{
+    if (B < 0 || V <= 0) return -1;
+    for (int b = 0; b < B; ++b) {
+        const int k_b = cu_q_len[b + 1] - cu_q_len[b] - 1;
+        if (k_b < 0 || k_b > ORACLE_K_MAX) return -1;
+        const size_t t_row0 = (size_t)cu_q_len[b];
+        const size_t d_row0 = (size_t)cu_q_len[b] - (size_t)b;
+        int m = 0;
+        int best = -1;
+        for (int i = 0; i <= k_b; ++i) {
+            const float *row = target_logits + (t_row0 + i) * V;
+            best = 0;
+            for (int v = 1; v < V; ++v)
+                if (row[v] > row[best]) best = v;
+            if (i == k_b) break;                         /* bonus position: nothing to compare */
+            const int32_t x = draft_tokens[d_row0 + i];
+            if (x < 0 || x >= V) return -1;
+            if (x != best) break;                        /* first mismatch: `best` is the correction */
+            ++m;
+        }
+        accepted_len[b] = m;
+        next_token[b] = best;
+        if (out_tokens) {
+            int32_t *row = out_tokens + (size_t)b * (ORACLE_K_MAX + 1);
+            for (int i = 0; i <= ORACLE_K_MAX; ++i) row[i] = -1;
+            for (int i = 0; i < m; ++i) row[i] = draft_tokens[d_row0 + i];
+            row[m] = best;
+        }
+        if (counters) {
+            counters[0] += k_b;
+            counters[1] += m;
+            counters[2] += (m + 1 < k_b) ? m + 1 : k_b;
+            counters[3] += m + 1;
+            counters[5] += 1;
+        }
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* Stochastic acceptance for a proposer that gives tokens but no         */
+/* distribution (Section 2.2: draft-model free speculation; Section 7:   */
+/* prompt lookup and single-candidate heads).  The draft distribution    */
+/* of position i is then the point mass on the proposed token x_i, and   */
+/* the rule of oracle_reject_sample reads: accept iff u < p_i(x_i); at   */
+/* the first rejection draw from norm(max(0, p - onehot(x))), which is   */
+/* p with x removed; if all are accepted draw the bonus from p_k.        */
+/* Uniforms, race and outputs as in oracle_reject_sample; dec_ratio      */
+/* holds p_i(x_i).                                                       */
+/* ------------------------------------------------------------------ */
+int oracle_reject_onehot(int32_t B, int32_t V, const float *target_logits,
+                         const int32_t *draft_tokens, const int32_t *cu_q_len,
+                         uint64_t seed, uint64_t step,
+                         int32_t *accepted_len, int32_t *next_token, int32_t *out_tokens,
+                         int64_t *counters, double *dec_u, double *dec_ratio,
+                         double *race_margin)
+{
+    if (B < 0 || V <= 0) return -1;
+    double *p = (double *)malloc(sizeof(double) * (size_t)V);
+    double *r = (double *)malloc(sizeof(double) * (size_t)V);
+    if (!p || !r) { free(p); free(r); return -1; }
+    for (int b = 0; b < B; ++b) {
+        const int k_b = cu_q_len[b + 1] - cu_q_len[b] - 1;
+        if (k_b < 0 || k_b > ORACLE_K_MAX) { free(p); free(r); return -1; }
+        const size_t t_row0 = (size_t)cu_q_len[b];
+        const size_t d_row0 = (size_t)cu_q_len[b] - (size_t)b;
+        if (dec_u) for (int i = 0; i < k_b; ++i) { dec_u[d_row0 + i] = NAN; dec_ratio[d_row0 + i] = NAN; }
+
+        int m = 0, near_ties = 0;
+        int32_t rejected = -1;
+        for (int i = 0; i < k_b; ++i) {
+            const int32_t x = draft_tokens[d_row0 + i];
+            if (x < 0 || x >= V) { free(p); free(r); return -1; }
+            oracle_softmax_row(target_logits + (t_row0 + i) * V, V, p);
+            const double ratio = p[x];                     /* q(x) = 1 */
+            const double u = oracle_u_accept(seed, step, b, i);
+            if (dec_u) { dec_u[d_row0 + i] = u; dec_ratio[d_row0 + i] = ratio; }
+            if (fabs(u - ratio) < ORACLE_NEAR_TIE) ++near_ties;
+            if (u < ratio) ++m; else { rejected = x; break; }
+        }
+        if (m == k_b) oracle_softmax_row(target_logits + (t_row0 + k_b) * V, V, p);
+        double total = 0.0;
+        for (int v = 0; v < V; ++v) { r[v] = (v == rejected) ? 0.0 : p[v]; total += r[v]; }
+        if (total == 0.0) for (int v = 0; v < V; ++v) r[v] = p[v];   /* p was the point mass on x (then u < 1 accepts: unreachable) */
+
+        int best = -1;
+        double best_score = -1.0;
+        for (int v = 0; v < V; ++v) {
+            if (r[v] <= 0.0) continue;
+            const double e = -log(oracle_u_race(seed, step, b, v));
+            const double s = (e == 0.0) ? INFINITY : r[v] / e;
+            if (s > best_score) { best_score = s; best = v; }
+        }
+        if (best < 0) { free(p); free(r); return -1; }
+        if (race_margin) {
+            double margin = INFINITY;
+            const double w_best = best_score;
+            for (int v = 0; v < V; ++v) {
+                if (v == best || r[v] <= 0.0) continue;
+                const double e = -log(oracle_u_race(seed, step, b, v));
+                const double s = (e == 0.0) ? INFINITY : r[v] / e;
+                double g;
+                if (isinf(best_score)) g = isinf(s) ? 0.0 : INFINITY;
+                else g = (best_score - s) / (w_best + s);
+                if (g < margin) margin = g;
+            }
+            race_margin[b] = margin;
+        }
+
+        accepted_len[b] = m;
+        next_token[b] = best;
+        if (out_tokens) {
+            int32_t *row = out_tokens + (size_t)b * (ORACLE_K_MAX + 1);
+            for (int i = 0; i <= ORACLE_K_MAX; ++i) row[i] = -1;
+            for (int i = 0; i < m; ++i) row[i] = draft_tokens[d_row0 + i];
+            row[m] = best;
+        }
+        if (counters) {
+            counters[0] += k_b;
+            counters[1] += m;
+            counters[2] += (m + 1 < k_b) ? m + 1 : k_b;
+            counters[3] += m + 1;
+            counters[4] += near_ties;
+            counters[5] += 1;
+        }
+    }
+    free(p); free(r);
+    return 0;
+}
+
 /* Eq. 4: expected generated length per request, bonus token included. */
 double oracle_expected_generated_len(double alpha, int32_t k)
 {

@@ -454,3 +454,113 @@ def test_synthetic_acceptance_levels_hit_their_targets():
             t = d + rng.standard_normal((6, V), dtype=np.float32) * np.float32(sigma)
             got = np.mean([oracle.accept_probability(t[i], d[i]) for i in range(6)])
             assert abs(got - alpha) < 0.04
+
+
+# ---------------------------------------------------------------------------
+# Greedy acceptance and acceptance against a point-mass draft (proposers that
+# give tokens but no distribution): Section 2.2 and Section 7 of the paper.
+# ---------------------------------------------------------------------------
+def _ragged_logits(seed, B, V, ks):
+    rng = np.random.default_rng(seed)
+    cu = np.concatenate([[0], np.cumsum(np.asarray(ks) + 1)]).astype(np.int32)
+    tl = (rng.standard_normal((int(cu[-1]), V)) * 3).astype(np.float32)
+    return rng, tl, cu
+
+
+def test_greedy_matches_numpy_argmax_walk():
+    """Brute force: leading run of draft tokens equal to the row arg-max, then that row's arg-max."""
+    B, V = 200, 37
+    ks = np.arange(B) % (K_MAX + 1)
+    rng, tl, cu = _ragged_logits(21, B, V, ks)
+    am = tl.argmax(axis=1)
+    toks = []
+    for b in range(B):
+        row0 = cu[b]
+        for i in range(ks[b]):
+            # mostly the arg-max (so that runs of several accepts occur), sometimes another token
+            toks.append(am[row0 + i] if rng.random() < 0.7 else rng.integers(V))
+    toks = np.asarray(toks, dtype=np.int32)
+    r = oracle.reject_greedy(tl, toks, cu)
+    for b in range(B):
+        row0, d0 = cu[b], cu[b] - b
+        m = 0
+        while m < ks[b] and toks[d0 + m] == am[row0 + m]:
+            m += 1
+        assert r.accepted_len[b] == m
+        assert r.next_token[b] == am[row0 + m]
+        want = list(toks[d0:d0 + m]) + [am[row0 + m]] + [-1] * (K_MAX - m)
+        assert r.out_tokens[b].tolist() == want
+    assert r.counters[0] == ks.sum() and r.counters[1] == r.accepted_len.sum()
+    assert r.counters[3] == r.accepted_len.sum() + B and r.counters[5] == B and r.counters[4] == 0
+
+
+def test_greedy_ties_take_the_lowest_id():
+    tl = np.zeros((2, 8), dtype=np.float32)
+    tl[0, [3, 5]] = 2.0        # two equal maxima: id 3 is the maximiser
+    tl[1, [6, 1]] = 1.0
+    cu = np.array([0, 2], dtype=np.int32)
+    r = oracle.reject_greedy(tl, np.array([5], dtype=np.int32), cu)
+    assert r.accepted_len[0] == 0 and r.next_token[0] == 3
+    r = oracle.reject_greedy(tl, np.array([3], dtype=np.int32), cu)
+    assert r.accepted_len[0] == 1 and r.next_token[0] == 1
+
+
+def test_greedy_equals_stochastic_rule_on_one_hot_target():
+    """A one-hot target makes the stochastic rule deterministic: the two rules agree."""
+    B, V, k = 50, 12, 3
+    rng = np.random.default_rng(5)
+    hot = rng.integers(V, size=B * (k + 1))
+    p = np.zeros((B * (k + 1), V))
+    p[np.arange(B * (k + 1)), hot] = 1.0
+    tl = np.stack([_logits_of(row) for row in p])
+    q = np.full(V, 1.0 / V)
+    dl = np.tile(_logits_of(q), (B * k, 1))
+    cu = (np.arange(B + 1) * (k + 1)).astype(np.int32)
+    toks = np.where(rng.random(B * k) < 0.6, hot.reshape(B, k + 1)[:, :k].reshape(-1), rng.integers(V, size=B * k)).astype(np.int32)
+    g = oracle.reject_greedy(tl, toks, cu)
+    s = oracle.reject_sample(tl, dl, toks, cu, 3, 1)
+    np.testing.assert_array_equal(g.accepted_len, s.accepted_len)
+    np.testing.assert_array_equal(g.next_token, s.next_token)
+    np.testing.assert_array_equal(g.out_tokens, s.out_tokens)
+
+
+def test_onehot_draft_equals_general_rule_with_point_mass_logits():
+    """The general rule fed draft logits that ARE a point mass gives the same decisions and tokens."""
+    B, V = 120, 40
+    ks = np.arange(B) % (K_MAX + 1)
+    rng, tl, cu = _ragged_logits(33, B, V, ks)
+    T = int(cu[-1])
+    toks = rng.integers(V, size=T - B).astype(np.int32)
+    dl = np.full((T - B, V), -1.0e4, dtype=np.float32)     # exp underflows to exactly 0 in double
+    dl[np.arange(T - B), toks] = 0.0
+    a = oracle.reject_onehot(tl, toks, cu, 77, 5)
+    b = oracle.reject_sample(tl, dl, toks, cu, 77, 5)
+    np.testing.assert_array_equal(a.accepted_len, b.accepted_len)
+    np.testing.assert_array_equal(a.next_token, b.next_token)
+    np.testing.assert_array_equal(a.out_tokens, b.out_tokens)
+    np.testing.assert_array_equal(a.counters, b.counters)
+    ev = ~np.isnan(a.dec_u)
+    np.testing.assert_array_equal(ev, ~np.isnan(b.dec_u))
+    np.testing.assert_allclose(a.dec_ratio[ev], b.dec_ratio[ev], rtol=1e-12)
+
+
+def test_onehot_draft_is_lossless_and_accepts_with_probability_p_x():
+    """Any fixed proposal x: P(accept) = p(x), and the first emitted token ~ p exactly."""
+    p = np.array([0.05, 0.35, 0.10, 0.20, 0.0, 0.30])
+    B = 150000
+    x = 3
+    tl, _, _, cu = _batch([p, [1 / 6] * 6], [p], [], 1, B)
+    toks = np.full(B, x, dtype=np.int32)
+    r = oracle.reject_onehot(tl, toks, cu, 1234, 0)
+    acc = r.accepted_len.mean()
+    assert abs(acc - p[x]) < 4.5 * math.sqrt(p[x] * (1 - p[x]) / B)
+    counts = np.bincount(r.out_tokens[:, 0], minlength=6)
+    assert counts[4] == 0
+    keep = p > 0
+    assert scipy.stats.chisquare(counts[keep], B * p[keep]).pvalue > 1e-3
+    # the correction never repeats the rejected token and is ~ p without x
+    rej = r.accepted_len == 0
+    cc = np.bincount(r.next_token[rej], minlength=6)
+    assert cc[x] == 0
+    res = p.copy(); res[x] = 0; res /= res.sum()
+    assert scipy.stats.chisquare(cc[res > 0], rej.sum() * res[res > 0]).pvalue > 1e-3
