@@ -111,7 +111,28 @@ typedef struct {
  * the next token is argmax_v r_v / (-log U'_v) (an exponential race, i.e. a
  * draw with probability proportional to the weights r_v; weights 0 never win,
  * equal scores go to the lowest v).
+ *
+ * accept_mode selects the acceptance rule (Section 2.2 describes the greedy
+ * one; Section 7 evaluates proposers that give tokens without a distribution):
+ *   SPEC_ACCEPT_SAMPLE       the rule above; needs draft_logits.
+ *   SPEC_ACCEPT_GREEDY       x_i is accepted iff it is the arg-max of target row
+ *                            i (lowest id among equal maxima); the next token is
+ *                            the arg-max of the row after the last accepted one.
+ *                            No random numbers; draft_logits is ignored (may be
+ *                            NULL); debug_u_ratio is not written.
+ *   SPEC_ACCEPT_POINT_DRAFT  the rule above with q_i the point mass on x_i:
+ *                            accept iff u_i < p_i(x_i); at the first rejection
+ *                            draw from p with the rejected token removed.
+ *                            draft_logits is ignored (may be NULL); debug_u_ratio
+ *                            holds u and p_i(x_i).
+ * Logits must not be NaN.
  */
+typedef enum {
+    SPEC_ACCEPT_SAMPLE = 0,
+    SPEC_ACCEPT_GREEDY = 1,
+    SPEC_ACCEPT_POINT_DRAFT = 2
+} spec_accept_mode;
+
 typedef struct {
     int32_t B, V, T;
     const float *target_logits;   /* [T][V]; request b owns rows cu_q_len[b] .. cu_q_len[b]+k_b */
@@ -133,6 +154,7 @@ typedef struct {
                                      [5] requests
                                      [6],[7] reserved, untouched */
     double *debug_u_ratio;        /* optional [T-B][2]: u and p/q of each evaluated accept test, NaN otherwise */
+    int32_t accept_mode;          /* spec_accept_mode */
 } spec_reject_args;
 
 /* Host-only: bytes of workspace the three calls below need for these shapes

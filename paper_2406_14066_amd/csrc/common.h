@@ -64,6 +64,7 @@ struct AttnParams {
 // 32-bit payload with the call's generation tag in the high half:
 //   statistics of one (row, vocabulary segment): 3 words: low and high half of
 //     sum_v 2^(x_v*log2(e) - off2) as fp64, and off2 (integer-valued base-2 offset) as fp32
+//     (greedy mode: the segment's largest logit as fp32 and its lowest id, third word unused)
 //   race partial of one (request, segment): 2 words: best score (fp32), its id
 //   race info of one request: m | k << 8 | near ties << 16
 constexpr int kStatWords = 3;
@@ -78,6 +79,7 @@ struct RejectPlan {
 
 struct RejectParams {
     int32_t B, V, T;
+    int32_t mode;   // spec_accept_mode
     const float *target_logits, *draft_logits;
     const int32_t *draft_tokens, *cu_q_len;
     uint32_t seed_lo, seed_hi, step_lo, step_hi24;

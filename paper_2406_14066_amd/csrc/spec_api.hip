@@ -79,7 +79,11 @@ spec_status validate_reject(const spec_reject_args *r)
     if (r->target_logits == nullptr || r->cu_q_len == nullptr || r->host_cu_q_len == nullptr ||
         r->accepted_len == nullptr || r->next_token == nullptr || r->counters == nullptr)
         return SPEC_EINVAL;
-    if (r->T > r->B && (r->draft_logits == nullptr || r->draft_tokens == nullptr)) return SPEC_EINVAL;
+    if (r->accept_mode != SPEC_ACCEPT_SAMPLE && r->accept_mode != SPEC_ACCEPT_GREEDY &&
+        r->accept_mode != SPEC_ACCEPT_POINT_DRAFT)
+        return SPEC_EINVAL;
+    if (r->T > r->B && r->draft_tokens == nullptr) return SPEC_EINVAL;
+    if (r->T > r->B && r->accept_mode == SPEC_ACCEPT_SAMPLE && r->draft_logits == nullptr) return SPEC_EINVAL;
     if (r->host_cu_q_len[0] != 0 || r->host_cu_q_len[r->B] != r->T) return SPEC_EINVAL;
     for (int b = 0; b < r->B; ++b) {
         const int q_len = r->host_cu_q_len[b + 1] - r->host_cu_q_len[b];
@@ -88,7 +92,7 @@ spec_status validate_reject(const spec_reject_args *r)
     if (r->V % 4 != 0) return SPEC_EUNSUPPORTED;  // rows are read as 16-byte vectors
     if (r->B > 65535 || 2 * (int64_t)r->T - r->B > 65535) return SPEC_EUNSUPPORTED;
     if ((reinterpret_cast<uintptr_t>(r->target_logits) & 15) != 0 ||
-        (reinterpret_cast<uintptr_t>(r->draft_logits) & 15) != 0)
+        (r->accept_mode == SPEC_ACCEPT_SAMPLE && (reinterpret_cast<uintptr_t>(r->draft_logits) & 15) != 0))
         return SPEC_EINVAL;
     return SPEC_OK;
 }
@@ -169,7 +173,8 @@ RejectPlan plan_reject(const spec_reject_args *r, size_t base)
 {
     RejectPlan pl;
     memset(&pl, 0, sizeof pl);
-    const int rows = 2 * r->T - r->B;
+    // logit rows that get a statistics pass: the draft rows only when there is a draft distribution
+    const int rows = r->accept_mode == SPEC_ACCEPT_SAMPLE ? 2 * r->T - r->B : r->T;
     // statistics: about 256 blocks in all, segments of >= 8192 logits, at most 32 per row
     int segs = (256 + rows - 1) / rows;
     const int max_by_len = (r->V + 8191) / 8192;
@@ -249,6 +254,7 @@ RejectParams reject_params(const spec_reject_args *r, const RejectPlan &pl, char
     RejectParams p;
     memset(&p, 0, sizeof p);
     p.B = r->B; p.V = r->V; p.T = r->T;
+    p.mode = r->accept_mode;
     p.target_logits = r->target_logits; p.draft_logits = r->draft_logits;
     p.draft_tokens = r->draft_tokens; p.cu_q_len = r->cu_q_len;
     p.seed_lo = (uint32_t)(r->philox_seed & 0xFFFFFFFFull);

@@ -269,6 +269,58 @@ __device__ __forceinline__ void stats_block(const RejectParams &p, int row, int 
     }
 }
 
+// Greedy mode: one (target row, segment): the largest logit and the lowest id that has it.
+__device__ __forceinline__ void argmax_block(const RejectParams &p, int row, int seg, RejectShared &sh)
+{
+    constexpr int UNROLL = 16;
+    const int tid = threadIdx.x;
+    const float *base = p.target_logits + (size_t)row * p.V;
+    const int v0 = seg * p.stat_seg_len;
+    const int v1 = min(p.V, v0 + p.stat_seg_len);
+    const float4 *vec = reinterpret_cast<const float4 *>(base + v0);
+    const int nvec = (v1 - v0) >> 2;
+    float best = -INFINITY;
+    int best_id = 0x7FFFFFFF;
+    for (int i = tid; i < nvec; i += kThreads * UNROLL) {
+        float4 x[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const int idx = i + u * kThreads;
+            x[u] = idx < nvec ? vec[idx] : make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const int idx = i + u * kThreads;
+            if (idx >= nvec) break;
+            const float e[4] = {x[u].x, x[u].y, x[u].z, x[u].w};
+            const int id0 = v0 + 4 * idx;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)   // ids rise within a thread: >= on -inf keeps the first, > keeps the lowest otherwise
+                if (e[j] > best || (e[j] == best && id0 + j < best_id)) { best = e[j]; best_id = id0 + j; }
+        }
+    }
+#pragma unroll
+    for (int o = kWave / 2; o > 0; o >>= 1) {
+        const float ov = __shfl_xor(best, o);
+        const int oi = __shfl_xor(best_id, o);
+        if (ov > best || (ov == best && oi < best_id)) { best = ov; best_id = oi; }
+    }
+    const int wave = tid / kWave, lane = tid % kWave;
+    if (lane == 0) { sh.best_score[wave] = best; sh.best_id[wave] = best_id; }
+    __syncthreads();
+    if (tid == 0) {
+#pragma unroll
+        for (int w = 1; w < kWaves; ++w) {
+            const float ov = sh.best_score[w];
+            const int oi = sh.best_id[w];
+            if (ov > best || (ov == best && oi < best_id)) { best = ov; best_id = oi; }
+        }
+        unsigned long long *dst = p.stats + 3 * ((size_t)row * p.stat_segments + seg);
+        publish_tagged(dst + 0, __float_as_uint(best), p.generation);
+        publish_tagged(dst + 1, (uint32_t)best_id, p.generation);
+    }
+}
+
 __device__ __forceinline__ float race_exponential(uint32_t word)
 {
     // U' = n * 2^-24 with n = (word >> 8) + 1 in [1, 2^24]; e = -log(U').
@@ -284,14 +336,15 @@ __device__ __forceinline__ float race_exponential(uint32_t word)
 }
 
 // The race over vocabulary ids [v0, v1) of one request: best r_v / e_v, e_v = -log(U'_v).
-// draft_row == nullptr: weights are the target probabilities (bonus token);
+// draft_row == nullptr: weights are the target probabilities (bonus token), with
+// exclude_id left out (point-mass draft: the rejected token; -1: none);
 // otherwise the positive part of p - q.
 //   p_v = corr_t * 2^(x_v * log2e + off_t), off_t = fp32(-log2-sum-exp), corr_t the
 //   factor lost by rounding off_t.  Ties keep the lowest id; weights <= 0 never win.
 // Returns the block's best (score, id) to every thread.
-__device__ void race_segment(const RejectParams &p, const float *target_row, const float *draft_row, int b, int v0,
-                             int v1, float off_t, float corr_t, float off_d, float corr_d, RejectShared &sh,
-                             float &win_score, int &win_id)
+__device__ void race_segment(const RejectParams &p, const float *target_row, const float *draft_row, int exclude_id,
+                             int b, int v0, int v1, float off_t, float corr_t, float off_d, float corr_d,
+                             RejectShared &sh, float &win_score, int &win_id)
 {
     float best_score = -1.0f;
     int best_id = 0x7FFFFFFF;
@@ -329,7 +382,7 @@ __device__ void race_segment(const RejectParams &p, const float *target_row, con
             const uint32_t word[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                if (r[e] > 0.0f) {
+                if (r[e] > 0.0f && v + e != exclude_id) {
                     const float ex = race_exponential(word[e]);
                     const float score = r[e] * __builtin_amdgcn_rcpf(ex);  // ex == 0 -> +inf
                     if (score > best_score) {  // ids rise within a thread: strict > keeps the lowest
@@ -384,7 +437,8 @@ __device__ bool accept_phase(const RejectParams &p, int b, RejectShared &sh, boo
     const int row_t0 = p.cu_q_len[b];
     const int k = p.cu_q_len[b + 1] - row_t0 - 1;
     const int row_d0 = row_t0 - b;
-    const int nrows = 2 * k + 1;
+    const bool has_draft_rows = p.mode == SPEC_ACCEPT_SAMPLE;
+    const int nrows = has_draft_rows ? 2 * k + 1 : k + 1;
     const int nstat = nrows * p.stat_segments;
 
     // the draft tokens' logits do not depend on the statistics: fetch them first
@@ -392,7 +446,7 @@ __device__ bool accept_phase(const RejectParams &p, int b, RejectShared &sh, boo
     if (tid < k) {
         const int x = p.draft_tokens[row_d0 + tid];
         tx = p.target_logits[(size_t)(row_t0 + tid) * p.V + x];
-        dx = p.draft_logits[(size_t)(row_d0 + tid) * p.V + x];
+        if (has_draft_rows) dx = p.draft_logits[(size_t)(row_d0 + tid) * p.V + x];
     }
 
     // poll and fetch in one: every word carries its own tag
@@ -424,7 +478,7 @@ __device__ bool accept_phase(const RejectParams &p, int b, RejectShared &sh, boo
     // accept tests, all evaluated in parallel; the chain is resolved below
     if (tid < k) {
         const double log2_p = (double)tx * kLog2eD - sh.lse2[tid];
-        const double log2_q = (double)dx * kLog2eD - sh.lse2[k + 1 + tid];
+        const double log2_q = has_draft_rows ? (double)dx * kLog2eD - sh.lse2[k + 1 + tid] : 0.0;   // point mass: q(x) = 1
         const double ratio = exp2(log2_p - log2_q);  // p = 0 -> 0, q = 0 < p -> inf, both 0 -> NaN (rejects)
         const uint4 w = philox4x32_10(make_uint4((uint32_t)tid, (uint32_t)b, p.step_lo, (p.step_hi24 << 8) | 0u),
                                       p.seed_lo, p.seed_hi);
@@ -460,6 +514,11 @@ __device__ void stats_role(const RejectParams &p, int item, RejectShared &sh)
 {
     const int rec = item / p.stat_segments;          // (request, row of the request)
     const int seg = item - rec * p.stat_segments;
+    if (p.mode != SPEC_ACCEPT_SAMPLE) {   // target rows only: rec is the row
+        if (p.mode == SPEC_ACCEPT_GREEDY) argmax_block(p, rec, seg, sh);
+        else stats_block(p, rec, seg, sh);
+        return;
+    }
     // largest b with 2 * cu_q_len[b] - b <= rec (rows of the requests before b).  Start from
     // where b would be if all requests had equally many rows, and walk: with equal draft
     // lengths that is one round of loads instead of the log2(B) dependent ones of a bisection.
@@ -481,6 +540,7 @@ struct RaceRows {
     const float *trow, *drow;
     float off_t, corr_t, off_d, corr_d;
     int m, k, row_d0;
+    int exclude;   // point-mass draft: the rejected token takes no part in the race
 };
 
 __device__ __forceinline__ RaceRows race_rows(const RejectParams &p, int b, const RejectShared &sh)
@@ -497,7 +557,9 @@ __device__ __forceinline__ RaceRows race_rows(const RejectParams &p, int b, cons
     rr.corr_d = 0.0f;
     rr.trow = p.target_logits + (size_t)(row_t0 + rr.m) * p.V;
     rr.drow = nullptr;
-    if (rr.m < rr.k) {
+    rr.exclude = -1;
+    if (rr.m < rr.k && p.mode == SPEC_ACCEPT_POINT_DRAFT) rr.exclude = p.draft_tokens[rr.row_d0 + rr.m];
+    if (rr.m < rr.k && p.mode == SPEC_ACCEPT_SAMPLE) {
         const double off_d_exact = -sh.lse2[rr.k + 1 + rr.m];
         rr.off_d = (float)off_d_exact;
         rr.corr_d = (float)exp2(off_d_exact - (double)rr.off_d);
@@ -524,7 +586,8 @@ __device__ void race_role(const RejectParams &p, int item, RejectShared &sh)
     const int v1 = min(p.V, v0 + p.race_seg_len);
     float win_score;
     int win_id;
-    race_segment(p, rr.trow, rr.drow, b, v0, v1, rr.off_t, rr.corr_t, rr.off_d, rr.corr_d, sh, win_score, win_id);
+    race_segment(p, rr.trow, rr.drow, rr.exclude, b, v0, v1, rr.off_t, rr.corr_t, rr.off_d, rr.corr_d, sh, win_score,
+                 win_id);
     if (tid == 0) {
         unsigned long long *dst = p.race_partial + 2 * ((size_t)b * p.race_segments + seg);
         publish_tagged(dst + 0, __float_as_uint(win_score), p.generation);
@@ -535,12 +598,78 @@ __device__ void race_role(const RejectParams &p, int item, RejectShared &sh)
     }
 }
 
+// Greedy mode, last stage of request b (there is no race): waits (bounded) for the
+// arg-max records of the request's k+1 target rows, accepts the leading run of draft
+// tokens that equal their row's arg-max, and emits the arg-max of the row after it.
+__device__ void greedy_final(const RejectParams &p, int b, RejectShared &sh)
+{
+    const int tid = threadIdx.x;
+    const int row_t0 = p.cu_q_len[b];
+    const int k = p.cu_q_len[b + 1] - row_t0 - 1;
+    const int row_d0 = row_t0 - b;
+    const int nstat = (k + 1) * p.stat_segments;
+    const bool ok = wait_all(p.spin_limit, [&] {
+        bool mine = true;
+        for (int i = tid; i < nstat; i += kThreads) {
+            const int ri = i / p.stat_segments;
+            const int sg = i - ri * p.stat_segments;
+            const unsigned long long *st = p.stats + 3 * ((size_t)(row_t0 + ri) * p.stat_segments + sg);
+            const unsigned long long w0 = fetch_u64(st), w1 = fetch_u64(st + 1);
+            mine = mine && tagged_ok(w0, p.generation) && tagged_ok(w1, p.generation);
+            sh.seg_off[ri][sg] = __uint_as_float((uint32_t)w0);
+            sh.seg_sum[ri][sg] = (double)(uint32_t)w1;   // the id, exactly
+        }
+        return mine;
+    });
+    if (!ok) {
+        if (tid == 0) { p.accepted_len[b] = -1; p.next_token[b] = -1; }
+        return;
+    }
+    if (tid <= k) {
+        float best = -INFINITY;
+        int best_id = 0x7FFFFFFF;
+        for (int sg = 0; sg < p.stat_segments; ++sg) {   // segments in rising id order: > keeps the lowest id
+            const float v = sh.seg_off[tid][sg];
+            const int id = (int)sh.seg_sum[tid][sg];
+            if (v > best || (v == best && id < best_id)) { best = v; best_id = id; }
+        }
+        sh.lse2[tid] = (double)(best_id == 0x7FFFFFFF ? 0 : best_id);
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int m = 0;
+        while (m < k && p.draft_tokens[row_d0 + m] == (int)sh.lse2[m]) ++m;
+        const int next = (int)sh.lse2[m];
+        p.accepted_len[b] = m;
+        p.next_token[b] = next;
+        if (p.out_tokens != nullptr) {
+            int32_t *row = p.out_tokens + (size_t)b * (SPEC_K_MAX + 1);
+            for (int i = 0; i <= SPEC_K_MAX; ++i)
+                row[i] = i < m ? p.draft_tokens[row_d0 + i] : (i == m ? next : -1);
+        }
+        atomicAdd(&p.counters[0], (unsigned long long)k);
+        atomicAdd(&p.counters[1], (unsigned long long)m);
+        atomicAdd(&p.counters[2], (unsigned long long)(m + 1 < k ? m + 1 : k));
+        atomicAdd(&p.counters[3], (unsigned long long)(m + 1));
+        atomicAdd(&p.counters[5], 1ull);
+    }
+    // clear this request's tags
+    for (int i = tid; i < 2 * nstat; i += kThreads) {
+        const int rec = i >> 1;
+        publish_u64(p.stats + 3 * ((size_t)row_t0 * p.stat_segments + rec) + (i & 1), 0ull);
+    }
+}
+
 // Last stage of request b (one item per request, after all race items):
 // waits (bounded) for the request's race segments, picks the winner, writes the
 // outputs and counters, and clears the request's tags so that a replay of the
 // same launch (HIP graph) starts clean.
 __device__ void final_role(const RejectParams &p, int b, RejectShared &sh)
 {
+    if (p.mode == SPEC_ACCEPT_GREEDY) {
+        greedy_final(p, b, sh);
+        return;
+    }
     const int tid = threadIdx.x;
     unsigned long long *part = p.race_partial + 2 * (size_t)b * p.race_segments;
     // poll and fetch in one: the race partials (race_segments <= 64: wavefront 0 holds
@@ -590,7 +719,7 @@ __device__ void final_role(const RejectParams &p, int b, RejectShared &sh)
             return;
         }
         const RaceRows rr = race_rows(p, b, sh);
-        race_segment(p, rr.trow, nullptr, b, 0, p.V, rr.off_t, rr.corr_t, 0.0f, 0.0f, sh, win_score, win_id);
+        race_segment(p, rr.trow, nullptr, -1, b, 0, p.V, rr.off_t, rr.corr_t, 0.0f, 0.0f, sh, win_score, win_id);
     }
     if (tid == 0) {
         p.accepted_len[b] = m;
@@ -608,7 +737,7 @@ __device__ void final_role(const RejectParams &p, int b, RejectShared &sh)
         atomicAdd(&p.counters[5], 1ull);
     }
     // clear this request's tags
-    const int nstat = (2 * k + 1) * p.stat_segments;
+    const int nstat = (p.mode == SPEC_ACCEPT_SAMPLE ? 2 * k + 1 : k + 1) * p.stat_segments;
     for (int i = tid; i < 3 * nstat; i += kThreads) {
         const int rec = i / 3;
         const int ri = rec / p.stat_segments;
@@ -1099,7 +1228,8 @@ hipError_t launch_step_fused(const AttnParams *attn, int row_tiles, const Reject
         rp = *reject;
         if (rp.stat_segments > kMaxStatSegments || rp.race_segments > kWave || rp.spin_limit < 1)
             return hipErrorInvalidValue;
-        n_stat = (2 * rp.T - rp.B) * rp.stat_segments;
+        if (rp.mode == SPEC_ACCEPT_GREEDY) rp.race_segments = 0;   // no race stage
+        n_stat = (rp.mode == SPEC_ACCEPT_SAMPLE ? 2 * rp.T - rp.B : rp.T) * rp.stat_segments;
         n_race = rp.B * rp.race_segments + rp.B;   // race segments, then one final item per request
     }
     if (attn != nullptr) {

@@ -20,7 +20,7 @@ class DeviceStep:
     """One verification step resident on the GPU."""
 
     def __init__(self, w: VerifyWorkload, kv_layout: int = sv.KV_TOKEN_MAJOR, device="cuda",
-                 with_debug: bool = True):
+                 with_debug: bool = True, accept_mode: int = sv.ACCEPT_SAMPLE):
         self.w = w
         self.device = device
         self.kv_layout = kv_layout
@@ -40,7 +40,8 @@ class DeviceStep:
         self.cu_q_len = torch.from_numpy(w.cu_q_len).to(device)
         self.out = torch.zeros((w.T, w.Hq, w.d), dtype=torch.float32, device=device)
         self.target_logits = torch.from_numpy(w.target_logits).to(device)
-        self.draft_logits = torch.from_numpy(w.draft_logits).to(device) if w.T > w.B else None
+        self.draft_logits = (torch.from_numpy(w.draft_logits).to(device)
+                             if (w.T > w.B and accept_mode == sv.ACCEPT_SAMPLE) else None)
         self.draft_tokens = torch.from_numpy(w.draft_tokens).to(device) if w.T > w.B else None
         self.accepted_len = torch.full((w.B,), -7, dtype=torch.int32, device=device)
         self.next_token = torch.full((w.B,), -7, dtype=torch.int32, device=device)
@@ -54,7 +55,8 @@ class DeviceStep:
         self.reject_args, self._keep_r = sv.make_reject_args(
             self.target_logits, self.draft_logits, self.draft_tokens, self.cu_q_len, w.cu_q_len,
             self.accepted_len, self.next_token, self.counters, philox_seed=w.philox_seed,
-            philox_step=w.philox_step, out_tokens=self.out_tokens, debug_u_ratio=self.debug)
+            philox_step=w.philox_step, out_tokens=self.out_tokens, debug_u_ratio=self.debug,
+            accept_mode=accept_mode)
         self.workspace = sv.alloc_workspace(sv.spec_verify_workspace_bytes(self.attn_args, self.reject_args), device)
 
     def run_attn(self, stream=None):

@@ -23,6 +23,7 @@ NUM_COUNTERS = 8
 SPEC_OK, SPEC_EINVAL, SPEC_EUNSUPPORTED, SPEC_EWORKSPACE, SPEC_EHIP = 0, -1, -2, -3, -4
 SPEC_F32, SPEC_BF16 = 0, 1
 KV_TOKEN_MAJOR, KV_MFMA = 0, 1
+ACCEPT_SAMPLE, ACCEPT_GREEDY, ACCEPT_POINT_DRAFT = 0, 1, 2   # spec_accept_mode
 
 COUNTER_NAMES = ("proposed", "accepted", "attempted", "emitted", "near_tie", "requests", "reserved6", "reserved7")
 
@@ -48,6 +49,7 @@ class RejectArgs(C.Structure):
         ("philox_seed", C.c_uint64), ("philox_step", C.c_uint64),
         ("accepted_len", C.c_void_p), ("next_token", C.c_void_p), ("out_tokens", C.c_void_p),
         ("counters", C.c_void_p), ("debug_u_ratio", C.c_void_p),
+        ("accept_mode", C.c_int32),
     ]
 
 
@@ -160,13 +162,14 @@ def make_attn_args(q, k_cache, v_cache, block_table, kv_len, cu_q_len, out, host
 
 
 def make_reject_args(target_logits, draft_logits, draft_tokens, cu_q_len, host_cu_q_len, accepted_len, next_token,
-                     counters, *, philox_seed: int, philox_step: int, out_tokens=None, debug_u_ratio=None):
+                     counters, *, philox_seed: int, philox_step: int, out_tokens=None, debug_u_ratio=None,
+                     accept_mode: int = 0):
     hc = _host_i32(host_cu_q_len)
     r = RejectArgs()
     r.B = hc.shape[0] - 1
     r.T, r.V = target_logits.shape
     r.target_logits = target_logits.data_ptr()
-    r.draft_logits = _dev_ptr(draft_logits) if r.T > r.B else None
+    r.draft_logits = _dev_ptr(draft_logits) if (r.T > r.B and accept_mode == ACCEPT_SAMPLE) else None
     r.draft_tokens = _dev_ptr(draft_tokens) if r.T > r.B else None
     r.cu_q_len = cu_q_len.data_ptr()
     r.host_cu_q_len = hc.ctypes.data
@@ -177,6 +180,7 @@ def make_reject_args(target_logits, draft_logits, draft_tokens, cu_q_len, host_c
     r.out_tokens = _dev_ptr(out_tokens)
     r.counters = counters.data_ptr()
     r.debug_u_ratio = _dev_ptr(debug_u_ratio)
+    r.accept_mode = accept_mode
     return r, (hc, target_logits, draft_logits, draft_tokens, cu_q_len, accepted_len, next_token, counters,
                out_tokens, debug_u_ratio)
 

@@ -155,3 +155,31 @@ def test_product_never_touches_the_oracle():
         if f.endswith((".py", ".c")):
             text = open(os.path.join(ROOT, "oracle", f)).read()
             assert "paper_2406_14066_amd" not in text and "spec_verify.h" not in text, f
+
+
+def test_accept_mode_validation():
+    """Modes without a draft distribution take a NULL draft_logits; an unknown mode is refused."""
+    cu = np.array([0, 3, 5], dtype=np.int32)
+    FAKE = 0x1000
+    def args(mode, draft_logits):
+        r = sv.RejectArgs()
+        r.B, r.V, r.T = 2, 64, 5
+        r.target_logits = FAKE
+        r.draft_logits = draft_logits
+        r.draft_tokens = FAKE
+        r.cu_q_len = FAKE
+        r.host_cu_q_len = cu.ctypes.data
+        r.accepted_len = FAKE
+        r.next_token = FAKE
+        r.counters = FAKE
+        r.accept_mode = mode
+        return r
+    assert sv.spec_validate_reject(args(sv.ACCEPT_SAMPLE, FAKE)) == sv.SPEC_OK
+    assert sv.spec_validate_reject(args(sv.ACCEPT_SAMPLE, None)) == sv.SPEC_EINVAL
+    assert sv.spec_validate_reject(args(sv.ACCEPT_GREEDY, None)) == sv.SPEC_OK
+    assert sv.spec_validate_reject(args(sv.ACCEPT_POINT_DRAFT, None)) == sv.SPEC_OK
+    assert sv.spec_validate_reject(args(3, FAKE)) == sv.SPEC_EINVAL
+    assert sv.spec_validate_reject(args(-1, FAKE)) == sv.SPEC_EINVAL
+    # fewer logit rows get a statistics pass without a draft distribution: the workspace is smaller
+    assert (sv.spec_verify_workspace_bytes(None, args(sv.ACCEPT_GREEDY, None))
+            <= sv.spec_verify_workspace_bytes(None, args(sv.ACCEPT_SAMPLE, FAKE)))
