@@ -39,6 +39,8 @@ def parse():
     ap.add_argument("--k", type=int, default=None, help="speculation length of the c3 sweep point")
     ap.add_argument("--alpha", type=float, default=None, help="acceptance level of the c3 sweep point")
     ap.add_argument("--rotate", type=int, default=0, help="device copies of KV/logits to cycle through (0 = auto)")
+    ap.add_argument("--accept-mode", default="sample", choices=["sample", "greedy", "point"],
+                    help="acceptance rule: the stochastic rule (headline), greedy, or stochastic against a point-mass draft")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="time the steps without per-kernel events (roofline then comes from a second loop)")
@@ -78,10 +80,12 @@ def main():
     if args.workload == "c3":
         kw = dict(k=args.k, alpha=args.alpha)
     w = W.config(args.workload, **kw)
-    ds = DeviceStep(w, kv_layout=sv.KV_MFMA, with_debug=False)
+    mode = {"sample": sv.ACCEPT_SAMPLE, "greedy": sv.ACCEPT_GREEDY, "point": sv.ACCEPT_POINT_DRAFT}[args.accept_mode]
+    ds = DeviceStep(w, kv_layout=sv.KV_MFMA, with_debug=False, accept_mode=mode)
 
     attn_bytes = w.attn_algorithmic_bytes()
-    rej_bytes = w.reject_algorithmic_bytes()
+    # without a draft distribution only the target rows are read
+    rej_bytes = w.reject_algorithmic_bytes() if mode == sv.ACCEPT_SAMPLE else w.T * w.V * 4
     step_bytes = attn_bytes + rej_bytes
     kv_bytes = 2 * ds.k_cache.numel() * ds.k_cache.element_size()
     nrot = args.rotate or max(2, int(np.ceil(1.2e9 / max(kv_bytes + rej_bytes, 1))))
@@ -100,7 +104,7 @@ def main():
                                   w.cu_q_len, Hkv=w.Hkv, kv_layout=sv.KV_MFMA)
         r, kr = sv.make_reject_args(tl, dl, ds.draft_tokens, ds.cu_q_len, w.cu_q_len, ds.accepted_len,
                                     ds.next_token, ds.counters, philox_seed=w.philox_seed,
-                                    philox_step=w.philox_step, out_tokens=ds.out_tokens)
+                                    philox_step=w.philox_step, out_tokens=ds.out_tokens, accept_mode=mode)
         variants.append((a, r, (ka, kr)))
 
     stream = torch.cuda.current_stream()
@@ -137,7 +141,7 @@ def main():
     kernel_us = {k: (1e3 * ms / n if n else None) for k, (ms, n) in kt.items()}
     step_us = kernel_us["step"]
     achieved = step_bytes / (step_us * 1e-6) / 1e9
-    traffic = traffic_from_profile(args.workload)
+    traffic = traffic_from_profile(args.workload) if mode == sv.ACCEPT_SAMPLE else None
 
     out = {
         "metric": "verified tokens/s per MI355X for spec-verify step",
@@ -156,6 +160,7 @@ def main():
             "workload": "%s: B=%d, L=%s, k=%s, Hq/Hkv=%d/%d, d=%d, bf16 paged KV (block 16, shuffled table), V=%d fp32 logits"
                         % (w.name, w.B, _span(w.kv_len), _span(w.k), w.Hq, w.Hkv, w.d, w.V),
             "kv_layout": "mfma-tiled pages",
+            "accept_mode": args.accept_mode,
             "rotated_copies": nrot,
             "verified_tokens_per_step": w.verified_tokens(),
             "emitted_tokens_per_step": emitted_per_step,
@@ -187,8 +192,13 @@ def main():
         t2 = time.perf_counter()
         oracle.verify_attn(w.q, w.k_pages, w.v_pages, w.block_table, w.kv_len, w.cu_q_len)
         t3 = time.perf_counter()
-        oracle.reject_sample(w.target_logits, w.draft_logits, w.draft_tokens, w.cu_q_len, w.philox_seed,
-                             w.philox_step)
+        if mode == sv.ACCEPT_SAMPLE:
+            oracle.reject_sample(w.target_logits, w.draft_logits, w.draft_tokens, w.cu_q_len, w.philox_seed,
+                                 w.philox_step)
+        elif mode == sv.ACCEPT_GREEDY:
+            oracle.reject_greedy(w.target_logits, w.draft_tokens, w.cu_q_len)
+        else:
+            oracle.reject_onehot(w.target_logits, w.draft_tokens, w.cu_q_len, w.philox_seed, w.philox_step)
         t4 = time.perf_counter()
         out["cpu_baseline"] = {
             "value": w.verified_tokens() / (t4 - t2),

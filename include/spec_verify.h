@@ -203,6 +203,74 @@ spec_status spec_kv_repack_mfma(const void *src_k, const void *src_v, void *dst_
 spec_status spec_profile_begin(int32_t max_launches);
 spec_status spec_profile_end(float *total_ms, int32_t *launches);
 
+/*
+ * Host-side speculation control (Section 4.1, "Using Goodput for Speculation"; no GPU
+ * work, no device pointers; all pointers are HOST pointers owned by the caller).
+ *
+ *   goodput (Eq. 1)     generated tokens of a step / time of the step
+ *   time (Eq. 2, 3)     T_draft + T_target, each forward pass modelled as
+ *                       c_context * N_context + c_batched * N_batched + c_fixed
+ *                       (N_context: tokens whose KV is cached, summed over the batch;
+ *                        N_batched: tokens scored in the pass)
+ *   generated (Eq. 4)   per request (1 - a^(k+1)) / (1 - a), a = token acceptance rate,
+ *                       bonus token included
+ */
+typedef struct {
+    double c_context;   /* seconds per context token  (Eq. 3's first coefficient)  */
+    double c_batched;   /* seconds per batched token  (Eq. 3's second coefficient) */
+    double c_fixed;     /* seconds per pass           (Eq. 3's constant)           */
+} spec_latency_model;
+
+/* Eq. 4.  alpha in [0,1], k >= 0; alpha == 1 gives k + 1.  NaN on bad arguments. */
+double spec_expected_generated_len(double alpha, int32_t k);
+
+/* Eq. 3 evaluated. */
+double spec_predict_latency(const spec_latency_model *model, double n_context, double n_batched);
+
+/* Ordinary least squares fit of Eq. 3 to n >= 3 measured passes (seconds[i] at
+ * n_context[i], n_batched[i]).  SPEC_EINVAL if the three columns are linearly
+ * dependent (e.g. every pass has the same N_batched) or an argument is NULL. */
+spec_status spec_fit_latency(const double *n_context, const double *n_batched, const double *seconds, int32_t n,
+                             spec_latency_model *model);
+
+/* Running estimate of the token acceptance rate (Section 4.1, "Accepted Length": a
+ * weighted average over past steps).  Feed it the step's counters: accepted =
+ * counters[1], attempted = counters[2] (accept tests actually evaluated; positions after
+ * the first rejection carry no information).  rate = sum_j w^(age_j) accepted_j /
+ * sum_j w^(age_j) attempted_j with decay w in (0,1]; steps with attempted == 0 leave it
+ * unchanged.  Zero-initialise the struct; rate is `prior` until something was observed. */
+typedef struct {
+    double accepted_weighted;
+    double attempted_weighted;
+} spec_acceptance_tracker;
+void spec_acceptance_update(spec_acceptance_tracker *tracker, int64_t accepted, int64_t attempted, double decay);
+double spec_acceptance_rate(const spec_acceptance_tracker *tracker, double prior);
+
+/* The search for the proposed length (Section 4.2, the listing "Finding k to maximize
+ * goodput").  For k = 0 .. max_k: skip k if the batch would need more than free_kv_tokens
+ * new KV slots (B * (k + 1)); generated(k) = sum_b Eq. 4(alpha_b, k);
+ * time(k) = target(N_context, B * (k + 1)) + T_draft(k), where T_draft(k) =
+ * k * draft(N_context, B) for a draft model (k sequential passes over the batch) or
+ * draft_fixed_seconds for a proposer whose cost does not depend on k (k > 0 only; a
+ * step with k = 0 runs no proposer).  Returns the k with the largest
+ * generated(k) / time(k) (the smallest such k on ties), or -1 on bad arguments or if no
+ * k fits.  k = 0 is ordinary decoding: the search can switch speculation off.
+ * goodput_per_k (optional, max_k + 1 entries) receives every candidate's value in
+ * tokens/s (NaN for a skipped k). */
+typedef struct {
+    int32_t B;
+    int32_t max_k;                  /* <= SPEC_K_MAX */
+    const int32_t *context_len;     /* [B] cached tokens per request */
+    const double *alpha;            /* [B], or [1] if alpha_per_request == 0 */
+    int32_t alpha_per_request;
+    spec_latency_model target;
+    int32_t draft_is_model;         /* 1: T_draft = k * draft(N_context, B); 0: draft_fixed_seconds */
+    spec_latency_model draft;
+    double draft_fixed_seconds;
+    int64_t free_kv_tokens;         /* < 0: unlimited */
+} spec_goodput_args;
+int32_t spec_argmax_goodput(const spec_goodput_args *args, double *goodput_per_k);
+
 const char *spec_status_string(spec_status status);
 
 /* Library version: major * 10000 + minor * 100 + patch. */

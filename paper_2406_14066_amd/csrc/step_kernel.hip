@@ -290,13 +290,13 @@ __device__ __forceinline__ void argmax_block(const RejectParams &p, int row, int
         }
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
-            const int idx = i + u * kThreads;
-            if (idx >= nvec) break;
-            const float e[4] = {x[u].x, x[u].y, x[u].z, x[u].w};
-            const int id0 = v0 + 4 * idx;
-#pragma unroll
-            for (int j = 0; j < 4; ++j)   // ids rise within a thread: >= on -inf keeps the first, > keeps the lowest otherwise
-                if (e[j] > best || (e[j] == best && id0 + j < best_id)) { best = e[j]; best_id = id0 + j; }
+            // vectors past the end were filled with -inf and ids that only grow: they change
+            // nothing unless the whole row is -inf, and then the lowest id still wins
+            const int id0 = v0 + 4 * (i + u * kThreads);
+            if (x[u].x > best || (x[u].x == best && id0 + 0 < best_id)) { best = x[u].x; best_id = id0 + 0; }
+            if (x[u].y > best || (x[u].y == best && id0 + 1 < best_id)) { best = x[u].y; best_id = id0 + 1; }
+            if (x[u].z > best || (x[u].z == best && id0 + 2 < best_id)) { best = x[u].z; best_id = id0 + 2; }
+            if (x[u].w > best || (x[u].w == best && id0 + 3 < best_id)) { best = x[u].w; best_id = id0 + 3; }
         }
     }
 #pragma unroll
@@ -342,7 +342,7 @@ __device__ __forceinline__ float race_exponential(uint32_t word)
 //   p_v = corr_t * 2^(x_v * log2e + off_t), off_t = fp32(-log2-sum-exp), corr_t the
 //   factor lost by rounding off_t.  Ties keep the lowest id; weights <= 0 never win.
 // Returns the block's best (score, id) to every thread.
-__device__ void race_segment(const RejectParams &p, const float *target_row, const float *draft_row, int exclude_id,
+__device__ __forceinline__ void race_segment(const RejectParams &p, const float *target_row, const float *draft_row, int exclude_id,
                              int b, int v0, int v1, float off_t, float corr_t, float off_d, float corr_d,
                              RejectShared &sh, float &win_score, int &win_id)
 {
@@ -431,7 +431,7 @@ __device__ __forceinline__ bool wait_all(int spin_limit, F probe)
 // recomputes it.  Waits (bounded) until all of the request's statistics carry this
 // call's tag.  Leaves log2-sum-exp per row in sh.lse2, m in sh.m, the near-tie count
 // in sh.near.  Returns false if the statistics never arrived.
-__device__ bool accept_phase(const RejectParams &p, int b, RejectShared &sh, bool write_debug)
+__device__ __forceinline__ bool accept_phase(const RejectParams &p, int b, RejectShared &sh, bool write_debug)
 {
     const int tid = threadIdx.x;
     const int row_t0 = p.cu_q_len[b];
@@ -510,7 +510,7 @@ __device__ bool accept_phase(const RejectParams &p, int b, RejectShared &sh, boo
 // Statistics items are ordered by request (its target rows, then its draft rows), so that
 // the first requests' statistics are complete early and their races can start while
 // later requests' rows are still being read.
-__device__ void stats_role(const RejectParams &p, int item, RejectShared &sh)
+__device__ __forceinline__ void stats_role(const RejectParams &p, int item, RejectShared &sh)
 {
     const int rec = item / p.stat_segments;          // (request, row of the request)
     const int seg = item - rec * p.stat_segments;
@@ -572,7 +572,7 @@ __device__ __forceinline__ RaceRows race_rows(const RejectParams &p, int b, cons
 // items in the grid, so the statistics blocks they wait for (inside accept_phase, with
 // a bound) were scheduled before them and never wait themselves: the wait ends.
 // Should the bound ever run out, the request's outputs are set to -1.
-__device__ void race_role(const RejectParams &p, int item, RejectShared &sh)
+__device__ __forceinline__ void race_role(const RejectParams &p, int item, RejectShared &sh)
 {
     const int tid = threadIdx.x;
     const int b = item / p.race_segments;
@@ -601,7 +601,7 @@ __device__ void race_role(const RejectParams &p, int item, RejectShared &sh)
 // Greedy mode, last stage of request b (there is no race): waits (bounded) for the
 // arg-max records of the request's k+1 target rows, accepts the leading run of draft
 // tokens that equal their row's arg-max, and emits the arg-max of the row after it.
-__device__ void greedy_final(const RejectParams &p, int b, RejectShared &sh)
+__device__ __forceinline__ void greedy_final(const RejectParams &p, int b, RejectShared &sh)
 {
     const int tid = threadIdx.x;
     const int row_t0 = p.cu_q_len[b];
@@ -664,7 +664,7 @@ __device__ void greedy_final(const RejectParams &p, int b, RejectShared &sh)
 // waits (bounded) for the request's race segments, picks the winner, writes the
 // outputs and counters, and clears the request's tags so that a replay of the
 // same launch (HIP graph) starts clean.
-__device__ void final_role(const RejectParams &p, int b, RejectShared &sh)
+__device__ __forceinline__ void final_role(const RejectParams &p, int b, RejectShared &sh)
 {
     if (p.mode == SPEC_ACCEPT_GREEDY) {
         greedy_final(p, b, sh);
@@ -776,7 +776,7 @@ struct OrderTable {
 };
 
 template <int NT, bool SPLIT_P>
-__device__ void attn_role(const AttnParams &p, OrderTable order, int item, AttnShared<NT> &sh)
+__device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order, int item, AttnShared<NT> &sh)
 {
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);

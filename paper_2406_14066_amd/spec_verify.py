@@ -57,6 +57,8 @@ EXPORTS = (
     "spec_verify_workspace_bytes", "spec_verify_attn", "spec_reject_sample", "spec_verify_step",
     "spec_validate_attn", "spec_validate_reject", "spec_kv_repack_mfma", "spec_status_string",
     "spec_verify_version", "spec_profile_begin", "spec_profile_end",
+    "spec_expected_generated_len", "spec_predict_latency", "spec_fit_latency",
+    "spec_acceptance_update", "spec_acceptance_rate", "spec_argmax_goodput",
 )
 NUM_KERNELS = 5
 KERNEL_NAMES = ("step", "attn", "attn_generic", "attn_combine", "reject")
@@ -245,3 +247,75 @@ def alloc_workspace(nbytes: int, device="cuda"):
     """A 256-byte aligned device buffer (torch's allocator aligns to 512)."""
     import torch
     return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+
+
+# ---------------------------------------------------------------------------
+# Host-side speculation control (no GPU work): thin wrappers, marshalling only.
+# ---------------------------------------------------------------------------
+class LatencyModel(C.Structure):
+    """Eq. 3 of the paper: seconds = c_context * N_context + c_batched * N_batched + c_fixed."""
+    _fields_ = [("c_context", C.c_double), ("c_batched", C.c_double), ("c_fixed", C.c_double)]
+
+
+class AcceptanceTracker(C.Structure):
+    _fields_ = [("accepted_weighted", C.c_double), ("attempted_weighted", C.c_double)]
+
+    def update(self, accepted: int, attempted: int, decay: float = 0.9) -> None:
+        _host_fn("spec_acceptance_update", None, [C.c_void_p, C.c_int64, C.c_int64, C.c_double])(
+            C.addressof(self), int(accepted), int(attempted), float(decay))
+
+    def rate(self, prior: float = 0.7) -> float:
+        return float(_host_fn("spec_acceptance_rate", C.c_double, [C.c_void_p, C.c_double])(
+            C.addressof(self), float(prior)))
+
+
+class GoodputArgs(C.Structure):
+    _fields_ = [("B", C.c_int32), ("max_k", C.c_int32), ("context_len", C.c_void_p), ("alpha", C.c_void_p),
+                ("alpha_per_request", C.c_int32), ("target", LatencyModel), ("draft_is_model", C.c_int32),
+                ("draft", LatencyModel), ("draft_fixed_seconds", C.c_double), ("free_kv_tokens", C.c_int64)]
+
+
+def _host_fn(name, restype, argtypes):
+    fn = getattr(lib(), name)
+    fn.restype = restype
+    fn.argtypes = argtypes
+    return fn
+
+
+def expected_generated_len(alpha: float, k: int) -> float:
+    return float(_host_fn("spec_expected_generated_len", C.c_double, [C.c_double, C.c_int32])(alpha, k))
+
+
+def fit_latency(n_context, n_batched, seconds) -> LatencyModel:
+    nc = np.ascontiguousarray(n_context, dtype=np.float64)
+    nb = np.ascontiguousarray(n_batched, dtype=np.float64)
+    t = np.ascontiguousarray(seconds, dtype=np.float64)
+    m = LatencyModel()
+    _check(_host_fn("spec_fit_latency", C.c_int, [C.c_void_p] * 3 + [C.c_int32, C.c_void_p])(
+        nc.ctypes.data, nb.ctypes.data, t.ctypes.data, len(t), C.addressof(m)), "spec_fit_latency")
+    return m
+
+
+def predict_latency(model: LatencyModel, n_context: float, n_batched: float) -> float:
+    return float(_host_fn("spec_predict_latency", C.c_double, [C.c_void_p, C.c_double, C.c_double])(
+        C.addressof(model), n_context, n_batched))
+
+
+def argmax_goodput(context_len, alpha, max_k: int, target: LatencyModel, draft: Optional[LatencyModel] = None,
+                   draft_fixed_seconds: float = 0.0, free_kv_tokens: int = -1):
+    """Returns (best k, goodput per k in tokens/s)."""
+    ctx = np.ascontiguousarray(context_len, dtype=np.int32)
+    al = np.ascontiguousarray(np.atleast_1d(alpha), dtype=np.float64)
+    a = GoodputArgs()
+    a.B, a.max_k = len(ctx), max_k
+    a.context_len, a.alpha = ctx.ctypes.data, al.ctypes.data
+    a.alpha_per_request = 1 if (len(al) == len(ctx) and len(ctx) > 1) else 0
+    a.target = target
+    a.draft_is_model = 1 if draft is not None else 0
+    if draft is not None:
+        a.draft = draft
+    a.draft_fixed_seconds = draft_fixed_seconds
+    a.free_kv_tokens = free_kv_tokens
+    curve = np.zeros(max_k + 1, dtype=np.float64)
+    k = int(_host_fn("spec_argmax_goodput", C.c_int32, [C.c_void_p, C.c_void_p])(C.addressof(a), curve.ctypes.data))
+    return k, curve

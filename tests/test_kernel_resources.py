@@ -1,0 +1,45 @@
+"""Build-time check of the step kernel's register and private-memory use (hipcc
+cross-compiles without a GPU).  Private memory in these kernels means that an argument
+struct or an unrolled register array fell back to memory: the launch then runs several
+times slower although every result stays correct, which no parity test notices."""
+import os
+import re
+import shutil
+import subprocess
+
+import pytest
+
+from paper_2406_14066_amd import build as B
+
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+
+
+@pytest.mark.skipif(shutil.which(HIPCC) is None and not os.path.exists(HIPCC), reason="hipcc not installed")
+def test_step_kernel_uses_no_private_memory_and_keeps_its_occupancy(tmp_path):
+    flags = [f for f in B.HIPCC_FLAGS if f not in ("-shared", "-fPIC")]
+    cmd = [HIPCC] + flags + ["-I", os.path.join(B.ROOT, "include"), "-I", B.CSRC, "-Rpass-analysis=kernel-resource-usage",
+                             "-c", "-o", str(tmp_path / "step.o"), os.path.join(B.CSRC, "step_kernel.hip")]
+    out = subprocess.run(cmd, check=True, capture_output=True, text=True).stderr
+    kernels = {}
+    name = None
+    for line in out.splitlines():
+        m = re.search(r"Function Name: \S*spec_step_kernelILi(\d)ELb(\d)ELb(\d)ELb(\d)E", line)
+        if m:
+            name = tuple(int(x) for x in m.groups())
+            kernels[name] = {}
+            continue
+        m = re.search(r"remark:\s+(VGPRs|ScratchSize \[bytes/lane\]|Occupancy \[waves/SIMD\]): (\d+)", line)
+        if m and name is not None:
+            kernels[name][m.group(1).split(" ")[0]] = int(m.group(2))
+    assert len(kernels) == 14, sorted(kernels)
+    for (nt, has_attn, has_reject, split_p), r in kernels.items():
+        if nt <= 2:
+            assert r["ScratchSize"] == 0, ((nt, has_attn, has_reject, split_p), r)
+        else:
+            assert r["ScratchSize"] <= 64, ((nt, has_attn, has_reject, split_p), r)   # three row tiles: a few spilled registers
+        if not has_attn:
+            assert r["Occupancy"] >= 4, r       # rejection-only launch
+        elif nt == 1:
+            assert r["Occupancy"] >= 3, r       # 168 registers or fewer
+        else:
+            assert r["Occupancy"] >= 2, r
