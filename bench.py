@@ -42,6 +42,7 @@ def parse():
     ap.add_argument("--accept-mode", default="sample", choices=["sample", "greedy", "point"],
                     help="acceptance rule: the stochastic rule (headline), greedy, or stochastic against a point-mass draft")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the same steps")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="time the steps without per-kernel events (roofline then comes from a second loop)")
     return ap.parse_args()
@@ -135,6 +136,32 @@ def main():
 
     sec_per_step = (t1 - t0) / args.steps
     value = w.verified_tokens() / sec_per_step
+
+    # The same steps replayed from one captured HIP graph (one step per rotated copy): what is
+    # left of the launch gaps when the host is out of the loop.  Reported beside the eager figure.
+    graph_info = None
+    if not args.no_graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            for i in range(nrot):
+                a, r, _ = variants[i]
+                sv.spec_verify_step(a, r, ds.workspace, torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        replays = max(args.steps // nrot, 1)
+        for _ in range(max(args.warmup // nrot, 1)):
+            graph.replay()
+        torch.cuda.synchronize()
+        g0 = time.perf_counter()
+        for _ in range(replays):
+            graph.replay()
+        torch.cuda.synchronize()
+        g1 = time.perf_counter()
+        graph_sec = (g1 - g0) / (replays * nrot)
+        graph_info = {"ms_per_step": graph_sec * 1e3, "value": w.verified_tokens() / graph_sec,
+                      "steps": replays * nrot, "steps_per_graph": nrot,
+                      "achieved_GBps": step_bytes / graph_sec / 1e9}
     res = ds.results()
     emitted_per_step = int(res["counters"][3]) // max(int(res["counters"][5]) // w.B, 1)
 
@@ -172,6 +199,7 @@ def main():
             "frac_of_peak": step_bytes / sec_per_step / 1e9 / HBM_PEAK_GBS,
         },
         "kernel_us": kernel_us,
+        "graph_replay": graph_info,
         "roofline": {
             "kernel": "spec_step_kernel (whole step in one launch: attention over the paged KV cache + rejection sampling)",
             "bound": "hbm",
