@@ -64,6 +64,10 @@ def _load():
         lib.oracle_reject_onehot.argtypes = (
             [c.c_int32, c.c_int32] + [c.c_void_p] * 3 + [c.c_uint64, c.c_uint64] + [c.c_void_p] * 7)
         lib.oracle_reject_onehot.restype = c.c_int
+        lib.oracle_kv_append.argtypes = [c.c_int32] * 8 + [c.c_void_p] * 7
+        lib.oracle_kv_append.restype = c.c_int
+        lib.oracle_kv_after_accept.argtypes = [c.c_int32] + [c.c_void_p] * 5
+        lib.oracle_kv_after_accept.restype = None
         lib.oracle_expected_generated_len.argtypes = [c.c_double, c.c_int32]
         lib.oracle_expected_generated_len.restype = c.c_double
         _lib = lib
@@ -223,3 +227,36 @@ def reject_onehot(target_logits, draft_tokens, cu_q_len, seed, step, counters=No
     if rc != 0:
         raise ValueError("oracle_reject_onehot: malformed arguments")
     return RejectResult(acc, nxt, out_tokens, cnt, dec_u[: T - B], dec_ratio[: T - B], margin)
+
+
+def kv_append(new_k, new_v, k_cache, v_cache, block_table, kv_len, cu_q_len, layout=0):
+    """Writes the step's new K/V rows [T,Hkv,d] into COPIES of the caches (flat or
+    [nb,Hkv,bs,d] arrays of nb*Hkv*bs*d elements; layout 0 token-major, 1 matrix-operand
+    tiles) and returns the copies."""
+    new_k = np.ascontiguousarray(new_k)
+    new_v = np.ascontiguousarray(new_v)
+    T, Hkv, d = new_k.shape
+    dtype = 0 if new_k.dtype == np.float32 else 1
+    kc = np.array(k_cache, copy=True, order="C")
+    vc = np.array(v_cache, copy=True, order="C")
+    assert kc.dtype == new_k.dtype and vc.dtype == new_k.dtype
+    bs = 16
+    nb = kc.size // (Hkv * bs * d)
+    bt = _carr(block_table, np.int32)
+    kl = _carr(kv_len, np.int32)
+    cu = _carr(cu_q_len, np.int32)
+    rc = _load().oracle_kv_append(kl.shape[0], Hkv, d, bs, nb, bt.shape[1], dtype, layout, _ptr(new_k), _ptr(new_v),
+                                  _ptr(kc), _ptr(vc), _ptr(bt), _ptr(kl), _ptr(cu))
+    if rc != 0:
+        raise ValueError("oracle_kv_append: malformed arguments")
+    return kc, vc
+
+
+def kv_after_accept(kv_len, cu_q_len, accepted_len):
+    kl = _carr(kv_len, np.int32)
+    cu = _carr(cu_q_len, np.int32)
+    acc = _carr(accepted_len, np.int32)
+    new_len = np.zeros_like(kl)
+    draft_next = np.zeros_like(kl)
+    _load().oracle_kv_after_accept(kl.shape[0], _ptr(kl), _ptr(cu), _ptr(acc), _ptr(new_len), _ptr(draft_next))
+    return new_len, draft_next

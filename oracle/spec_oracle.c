@@ -502,6 +502,75 @@ int oracle_reject_onehot(int32_t B, int32_t V, const float *target_logits,
     return 0;
 }
 
+/* ------------------------------------------------------------------ */
+/* The steps either side of the path (Section 5.1, "KV Cache of Bonus    */
+/* Tokens"): before scoring, the K and V rows of this step's q_len        */
+/* query positions are written into the paged cache at token positions   */
+/* kv_len - q_len .. kv_len - 1; after acceptance the cache logically     */
+/* keeps the first query position and the m accepted draft tokens, so    */
+/* the rejected tail is dropped: new_kv_len = kv_len - (k - m).  The      */
+/* draft model's own cache then lacks one token (the emitted one) after   */
+/* a rejection, and two after full acceptance (the last draft token,      */
+/* whose entry was never generated, and the bonus token).                 */
+/*                                                                        */
+/* Element (page, kvh, slot s, dim c) of one (page, KV head) sits at      */
+/*   layout 0 (token-major)  s * d + c                                    */
+/*   layout 1 (matrix-operand tiles, bf16, 16-token pages)                */
+/*       K: (c / 8) * 128 + s * 8 + c % 8                                 */
+/*       V: ((((c/32) * 4 + s/4) * 16 + c%16) * 2 + (c/16)%2) * 4 + s%4   */
+/* in units of elements from the start of that (page, KV head), which     */
+/* holds bs * d elements; (page, kvh) starts at (page*Hkv + kvh)*bs*d.    */
+/* ------------------------------------------------------------------ */
+static size_t oracle_kv_offset(int layout, int is_v, int bs, int d, int s, int c)
+{
+    if (layout == 0) return (size_t)s * d + c;
+    (void)bs;
+    if (!is_v) return (size_t)(c / 8) * 128 + (size_t)s * 8 + c % 8;
+    return ((((size_t)(c / 32) * 4 + s / 4) * 16 + c % 16) * 2 + (c / 16) % 2) * 4 + s % 4;
+}
+
+int oracle_kv_append(int32_t B, int32_t Hkv, int32_t d, int32_t bs, int32_t num_blocks,
+                     int32_t max_blocks, int32_t dtype, int32_t layout,
+                     const void *new_k, const void *new_v, void *k_cache, void *v_cache,
+                     const int32_t *block_table, const int32_t *kv_len, const int32_t *cu_q_len)
+{
+    if (layout != 0 && (layout != 1 || bs != 16 || dtype != 1 || d % 32 != 0)) return -1;
+    const size_t esz = dtype == 1 ? 2 : 4;
+    for (int b = 0; b < B; ++b) {
+        const int q_len = cu_q_len[b + 1] - cu_q_len[b];
+        if (q_len < 1 || kv_len[b] < q_len) return -1;
+        for (int j = 0; j < q_len; ++j) {
+            const int pos = kv_len[b] - q_len + j;
+            if (pos / bs >= max_blocks) return -1;
+            const int page = block_table[(size_t)b * max_blocks + pos / bs];
+            if (page < 0 || page >= num_blocks) return -1;
+            const int s = pos % bs;
+            for (int h = 0; h < Hkv; ++h) {
+                const size_t head = ((size_t)page * Hkv + h) * (size_t)bs * d;
+                const size_t src = (((size_t)cu_q_len[b] + j) * Hkv + h) * d;
+                for (int c = 0; c < d; ++c) {
+                    memcpy((char *)k_cache + (head + oracle_kv_offset(layout, 0, bs, d, s, c)) * esz,
+                           (const char *)new_k + (src + c) * esz, esz);
+                    memcpy((char *)v_cache + (head + oracle_kv_offset(layout, 1, bs, d, s, c)) * esz,
+                           (const char *)new_v + (src + c) * esz, esz);
+                }
+            }
+        }
+    }
+    return 0;
+}
+
+void oracle_kv_after_accept(int32_t B, const int32_t *kv_len, const int32_t *cu_q_len,
+                            const int32_t *accepted_len, int32_t *new_kv_len, int32_t *draft_next_len)
+{
+    for (int b = 0; b < B; ++b) {
+        const int k = cu_q_len[b + 1] - cu_q_len[b] - 1;
+        const int m = accepted_len[b];
+        new_kv_len[b] = kv_len[b] - (k - m);
+        draft_next_len[b] = (k > 0 && m == k) ? 2 : 1;
+    }
+}
+
 /* Eq. 4: expected generated length per request, bonus token included. */
 double oracle_expected_generated_len(double alpha, int32_t k)
 {

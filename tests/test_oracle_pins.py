@@ -564,3 +564,82 @@ def test_onehot_draft_is_lossless_and_accepts_with_probability_p_x():
     assert cc[x] == 0
     res = p.copy(); res[x] = 0; res /= res.sum()
     assert scipy.stats.chisquare(cc[res > 0], rej.sum() * res[res > 0]).pvalue > 1e-3
+
+
+# ---------------------------------------------------------------------------
+# KV append and the bookkeeping after acceptance (Section 5.1 of the paper).
+# ---------------------------------------------------------------------------
+def _append_case(dtype):
+    return W.make_workload("app", B=4, Hq=4, Hkv=2, d=64 if dtype == "f32" else 128, V=8, dtype=dtype,
+                           kv_len=[37, 16, 300, 5], k=[3, 0, 8, 4], draft_std=1.0, sigma=1.0, data_seed=77,
+                           philox_seed=1, with_logits=False)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_kv_append_token_major_restores_erased_rows(dtype):
+    """Erase the last q_len tokens of every request from the pools, append them again from a
+    packed [T,Hkv,d] array: the pools, and the attention output, are what they were."""
+    w = _append_case(dtype)
+    T = w.T
+    new_k = np.zeros((T, w.Hkv, w.d), dtype=w.k_pages.dtype)
+    new_v = np.zeros_like(new_k)
+    kc, vc = w.k_pages.copy(), w.v_pages.copy()
+    for b in range(w.B):
+        for j in range(int(w.q_len[b])):
+            pos = int(w.kv_len[b]) - int(w.q_len[b]) + j
+            page, slot = int(w.block_table[b, pos // 16]), pos % 16
+            new_k[w.cu_q_len[b] + j] = kc[page, :, slot, :]
+            new_v[w.cu_q_len[b] + j] = vc[page, :, slot, :]
+            kc[page, :, slot, :] = 0
+            vc[page, :, slot, :] = 0
+    assert not np.array_equal(kc, w.k_pages)
+    k2, v2 = oracle.kv_append(new_k, new_v, kc, vc, w.block_table, w.kv_len, w.cu_q_len, layout=0)
+    np.testing.assert_array_equal(k2, w.k_pages)
+    np.testing.assert_array_equal(v2, w.v_pages)
+    np.testing.assert_array_equal(kc[kc != 0], kc[kc != 0])     # inputs were copied, not written
+    a = oracle.verify_attn(w.q, k2, v2, w.block_table, w.kv_len, w.cu_q_len)
+    b = oracle.verify_attn(w.q, w.k_pages, w.v_pages, w.block_table, w.kv_len, w.cu_q_len)
+    np.testing.assert_array_equal(a, b)
+
+
+def test_kv_append_tiled_layout_offsets():
+    """The matrix-operand layout, checked against offsets worked out by hand from its definition
+    (K: [d/8][16 tokens][8 dims]; V: [d/32][4 token groups][16 dims][2 dim halves][4 tokens])."""
+    B, Hkv, d = 1, 1, 128
+    cu = np.array([0, 1], dtype=np.int32)
+    bt = np.array([[0]], dtype=np.int32)
+    seen_k, seen_v = set(), set()
+    hand = {  # (slot, dim) -> (K offset, V offset)
+        (0, 0): (0, 0),
+        (3, 9): (1 * 128 + 3 * 8 + 1, (((0 * 4 + 0) * 16 + 9) * 2 + 0) * 4 + 3),
+        (7, 16): (2 * 128 + 7 * 8 + 0, (((0 * 4 + 1) * 16 + 0) * 2 + 1) * 4 + 3),
+        (15, 127): (15 * 128 + 15 * 8 + 7, (((3 * 4 + 3) * 16 + 15) * 2 + 1) * 4 + 3),
+        (5, 40): (5 * 128 + 5 * 8 + 0, (((1 * 4 + 1) * 16 + 8) * 2 + 0) * 4 + 1),
+    }
+    for slot in range(16):
+        row_k = (np.arange(d) + 1 + 200 * slot).astype(np.uint16)       # distinct non-zero values
+        row_v = (np.arange(d) + 1 + 200 * slot + 5000).astype(np.uint16)
+        kc = np.zeros(16 * d, dtype=np.uint16)
+        vc = np.zeros(16 * d, dtype=np.uint16)
+        k2, v2 = oracle.kv_append(row_k.reshape(1, 1, d), row_v.reshape(1, 1, d), kc, vc, bt,
+                                  np.array([slot + 1], dtype=np.int32), cu, layout=1)
+        assert np.count_nonzero(k2) == d and np.count_nonzero(v2) == d
+        for c in range(d):
+            ok = int(np.nonzero(k2 == row_k[c])[0][0])
+            ov = int(np.nonzero(v2 == row_v[c])[0][0])
+            seen_k.add(ok)
+            seen_v.add(ov)
+            if (slot, c) in hand:
+                assert (ok, ov) == hand[(slot, c)], (slot, c, ok, ov)
+    assert seen_k == set(range(16 * d)) and seen_v == set(range(16 * d))     # a bijection onto the 4 KB
+
+
+def test_kv_bookkeeping_after_accept():
+    kv = np.array([100, 50, 33, 20], dtype=np.int32)
+    cu = np.array([0, 3, 6, 7, 12], dtype=np.int32)     # k = 2, 2, 0, 4
+    acc = np.array([2, 0, 0, 3], dtype=np.int32)
+    new_len, draft_next = oracle.kv_after_accept(kv, cu, acc)
+    # Section 5.1's example (k = 2): all accepted -> nothing dropped, the draft model is two tokens
+    # behind; a rejection -> the rejected tail is dropped and it is one behind
+    assert new_len.tolist() == [100, 48, 33, 19]
+    assert draft_next.tolist() == [2, 1, 1, 1]
