@@ -155,6 +155,13 @@ typedef struct {
                                      [6],[7] reserved, untouched */
     double *debug_u_ratio;        /* optional [T-B][2]: u and p/q of each evaluated accept test, NaN otherwise */
     int32_t accept_mode;          /* spec_accept_mode */
+    /* Cache bookkeeping after acceptance (Section 5.1, "KV Cache of Bonus Tokens"); all three
+     * optional (NULL), kv_len is needed if either output is given: */
+    const int32_t *kv_len;        /* [B] the attention's kv_len (includes this step's q_len positions) */
+    int32_t *new_kv_len;          /* [B] out: kv_len - (k_b - m_b): the rejected tail is dropped; the next
+                                     token is not in the cache yet (it is the next step's first query) */
+    int32_t *draft_next_len;      /* [B] out: tokens the draft model's cache is behind by: 2 after full
+                                     acceptance of k_b > 0 tokens (last draft token + bonus), else 1 */
 } spec_reject_args;
 
 /* Host-only: bytes of workspace the three calls below need for these shapes
@@ -179,6 +186,28 @@ spec_status spec_verify_step(const spec_attn_args *attn, const spec_reject_args 
 /* Host-only validation, exactly what the calls above run first. */
 spec_status spec_validate_attn(const spec_attn_args *attn);
 spec_status spec_validate_reject(const spec_reject_args *reject);
+
+/*
+ * The step before the path (Section 5.1): the K and V rows of this step's query
+ * positions enter the paged cache.  Row cu_q_len[b] + j of new_k / new_v
+ * ([T][Hkv][d], same dtype as the cache) is written to token position
+ * kv_len[b] - q_len[b] + j of request b, through the block table, in the given
+ * page layout.  Everything else in the pools is left as it is.  Device pointers;
+ * host_kv_len / host_cu_q_len are HOST copies used for validation only.
+ * SPEC_EINVAL if a position falls outside the request's block-table row.
+ */
+typedef struct {
+    int32_t B, Hkv, d, num_blocks, max_blocks_per_req, T;
+    int32_t dtype;                /* spec_dtype */
+    int32_t kv_layout;            /* spec_kv_layout (SPEC_KV_MFMA: bf16, d % 32 == 0) */
+    const void *new_k, *new_v;    /* [T][Hkv][d] */
+    void *k_cache, *v_cache;      /* the pools, written in place */
+    const int32_t *block_table;   /* [B][max_blocks_per_req] */
+    const int32_t *kv_len;        /* [B], INCLUDING the rows being appended */
+    const int32_t *cu_q_len;      /* [B+1] */
+    const int32_t *host_kv_len, *host_cu_q_len;
+} spec_kv_append_args;
+spec_status spec_kv_append(const spec_kv_append_args *args, void *hip_stream);
 
 /* Re-tile a token-major bf16 page pool [num_blocks][Hkv][16][d] into the
  * SPEC_KV_MFMA layout (dst_k, dst_v; same byte sizes; must not alias the sources). */

@@ -180,7 +180,46 @@ __global__ void kv_repack_kernel(const uint16_t *src_k, const uint16_t *src_v, u
     for (int e = 0; e < 8; ++e) dst_v[head * d * SPEC_BLOCK_SIZE + v_tiled_offset(g * 8 + e, slot)] = src_v[src + e];
 }
 
+// KV append: one thread per (packed row, kv head, group of 8 elements).
+template <typename T>
+__global__ void kv_append_kernel(KvAppendParams p)
+{
+    const int groups = p.d >> 3;
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t total = (size_t)p.T * p.Hkv * groups;
+    if (idx >= total) return;
+    const int g = (int)(idx % groups);
+    const int kvh = (int)((idx / groups) % p.Hkv);
+    const int row = (int)(idx / ((size_t)groups * p.Hkv));
+    const int b = find_request(p.cu_q_len, p.B, row);
+    const int q_len = p.cu_q_len[b + 1] - p.cu_q_len[b];
+    const int pos = p.kv_len[b] - q_len + (row - p.cu_q_len[b]);
+    const int page = p.block_table[(size_t)b * p.max_blocks_per_req + pos / SPEC_BLOCK_SIZE];
+    const int slot = pos % SPEC_BLOCK_SIZE;
+    const T *sk = static_cast<const T *>(p.new_k) + ((size_t)row * p.Hkv + kvh) * p.d + g * 8;
+    const T *sv = static_cast<const T *>(p.new_v) + ((size_t)row * p.Hkv + kvh) * p.d + g * 8;
+    T *dk = static_cast<T *>(p.k_cache);
+    T *dv = static_cast<T *>(p.v_cache);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const int c = g * 8 + e;
+        dk[k_index(p.kv_layout, page, p.Hkv, kvh, slot, c, p.d)] = sk[e];
+        dv[v_index(p.kv_layout, page, p.Hkv, kvh, slot, c, p.d)] = sv[e];
+    }
+}
+
 }  // namespace
+
+hipError_t launch_kv_append(const KvAppendParams &p, hipStream_t stream)
+{
+    const size_t total = (size_t)p.T * p.Hkv * (p.d >> 3);
+    const unsigned blocks = (unsigned)((total + 255) / 256);
+    if (p.elem_bytes == 4)
+        hipLaunchKernelGGL(kv_append_kernel<float>, dim3(blocks), dim3(256), 0, stream, p);
+    else
+        hipLaunchKernelGGL(kv_append_kernel<uint16_t>, dim3(blocks), dim3(256), 0, stream, p);
+    return hipGetLastError();
+}
 
 hipError_t launch_attn_generic(const AttnParams &p, int dtype, hipStream_t stream)
 {

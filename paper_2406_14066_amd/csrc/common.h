@@ -86,6 +86,8 @@ struct RejectParams {
     int32_t *accepted_len, *next_token, *out_tokens;
     unsigned long long *counters;
     double *debug_u_ratio;
+    const int32_t *kv_len;               // cache bookkeeping after acceptance (optional)
+    int32_t *new_kv_len, *draft_next_len;
     int32_t stat_segments, stat_seg_len;
     int32_t race_segments, race_seg_len;
     int32_t spin_limit;                  // polls a race block spends waiting for its request's accept phase
@@ -111,6 +113,13 @@ hipError_t launch_step_fused(const AttnParams *attn, int row_tiles, const Reject
 // Generic attention path: partial kernel + combine kernel.
 hipError_t launch_attn_generic(const AttnParams &p, int dtype, hipStream_t stream);
 hipError_t launch_attn_combine(const AttnParams &p, hipStream_t stream);
+struct KvAppendParams {
+    int32_t B, Hkv, d, max_blocks_per_req, T, kv_layout, elem_bytes;
+    const void *new_k, *new_v;
+    void *k_cache, *v_cache;
+    const int32_t *block_table, *kv_len, *cu_q_len;
+};
+hipError_t launch_kv_append(const KvAppendParams &p, hipStream_t stream);
 hipError_t launch_kv_repack(const void *src_k, const void *src_v, void *dst_k, void *dst_v, int32_t num_blocks,
                             int32_t Hkv, int32_t d, hipStream_t stream);
 

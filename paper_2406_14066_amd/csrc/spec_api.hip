@@ -89,6 +89,7 @@ spec_status validate_reject(const spec_reject_args *r)
         const int q_len = r->host_cu_q_len[b + 1] - r->host_cu_q_len[b];
         if (q_len < 1 || q_len > SPEC_K_MAX + 1) return SPEC_EINVAL;
     }
+    if ((r->new_kv_len != nullptr || r->draft_next_len != nullptr) && r->kv_len == nullptr) return SPEC_EINVAL;
     if (r->V % 4 != 0) return SPEC_EUNSUPPORTED;  // rows are read as 16-byte vectors
     if (r->B > 65535 || 2 * (int64_t)r->T - r->B > 65535) return SPEC_EUNSUPPORTED;
     if ((reinterpret_cast<uintptr_t>(r->target_logits) & 15) != 0 ||
@@ -264,6 +265,7 @@ RejectParams reject_params(const spec_reject_args *r, const RejectPlan &pl, char
     p.accepted_len = r->accepted_len; p.next_token = r->next_token; p.out_tokens = r->out_tokens;
     p.counters = reinterpret_cast<unsigned long long *>(r->counters);
     p.debug_u_ratio = r->debug_u_ratio;
+    p.kv_len = r->kv_len; p.new_kv_len = r->new_kv_len; p.draft_next_len = r->draft_next_len;
     p.stat_segments = pl.stat_segments; p.stat_seg_len = pl.stat_seg_len;
     p.race_segments = pl.race_segments; p.race_seg_len = pl.race_seg_len;
     p.spin_limit = 1 << 20;   // about a second of polling; never reached in a healthy launch
@@ -393,6 +395,34 @@ spec_status spec_verify_step(const spec_attn_args *attn, const spec_reject_args 
     const hipError_t err =
         timed(SPEC_KERNEL_REJECT, stream, [&] { return launch_step_fused(nullptr, 0, &rp, nullptr, stream); });
     return err == hipSuccess ? SPEC_OK : SPEC_EHIP;
+}
+
+spec_status spec_kv_append(const spec_kv_append_args *a, void *hip_stream)
+{
+    if (a == nullptr || a->B < 1 || a->Hkv < 1 || a->T < a->B || a->num_blocks < 1 || a->max_blocks_per_req < 1)
+        return SPEC_EINVAL;
+    if (a->new_k == nullptr || a->new_v == nullptr || a->k_cache == nullptr || a->v_cache == nullptr ||
+        a->block_table == nullptr || a->kv_len == nullptr || a->cu_q_len == nullptr || a->host_kv_len == nullptr ||
+        a->host_cu_q_len == nullptr)
+        return SPEC_EINVAL;
+    if (a->dtype != SPEC_F32 && a->dtype != SPEC_BF16) return SPEC_EINVAL;
+    if (a->kv_layout != SPEC_KV_TOKEN_MAJOR && a->kv_layout != SPEC_KV_MFMA) return SPEC_EINVAL;
+    if (a->d != 64 && a->d != 128) return SPEC_EUNSUPPORTED;
+    if (a->kv_layout == SPEC_KV_MFMA && a->dtype != SPEC_BF16) return SPEC_EUNSUPPORTED;
+    if (a->host_cu_q_len[0] != 0 || a->host_cu_q_len[a->B] != a->T) return SPEC_EINVAL;
+    for (int b = 0; b < a->B; ++b) {
+        const int q_len = a->host_cu_q_len[b + 1] - a->host_cu_q_len[b];
+        if (q_len < 1 || q_len > SPEC_K_MAX + 1 || a->host_kv_len[b] < q_len) return SPEC_EINVAL;
+        if ((a->host_kv_len[b] + SPEC_BLOCK_SIZE - 1) / SPEC_BLOCK_SIZE > a->max_blocks_per_req) return SPEC_EINVAL;
+    }
+    KvAppendParams p;
+    memset(&p, 0, sizeof p);
+    p.B = a->B; p.Hkv = a->Hkv; p.d = a->d; p.max_blocks_per_req = a->max_blocks_per_req; p.T = a->T;
+    p.kv_layout = a->kv_layout;
+    p.elem_bytes = a->dtype == SPEC_BF16 ? 2 : 4;
+    p.new_k = a->new_k; p.new_v = a->new_v; p.k_cache = a->k_cache; p.v_cache = a->v_cache;
+    p.block_table = a->block_table; p.kv_len = a->kv_len; p.cu_q_len = a->cu_q_len;
+    return launch_kv_append(p, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? SPEC_OK : SPEC_EHIP;
 }
 
 spec_status spec_kv_repack_mfma(const void *src_k, const void *src_v, void *dst_k, void *dst_v, int32_t num_blocks,

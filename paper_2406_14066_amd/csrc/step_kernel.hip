@@ -642,6 +642,8 @@ __device__ __forceinline__ void greedy_final(const RejectParams &p, int b, Rejec
         const int next = (int)sh.lse2[m];
         p.accepted_len[b] = m;
         p.next_token[b] = next;
+        if (p.new_kv_len != nullptr) p.new_kv_len[b] = p.kv_len[b] - (k - m);
+        if (p.draft_next_len != nullptr) p.draft_next_len[b] = (k > 0 && m == k) ? 2 : 1;
         if (p.out_tokens != nullptr) {
             int32_t *row = p.out_tokens + (size_t)b * (SPEC_K_MAX + 1);
             for (int i = 0; i <= SPEC_K_MAX; ++i)
@@ -724,6 +726,8 @@ __device__ __forceinline__ void final_role(const RejectParams &p, int b, RejectS
     if (tid == 0) {
         p.accepted_len[b] = m;
         p.next_token[b] = win_id;
+        if (p.new_kv_len != nullptr) p.new_kv_len[b] = p.kv_len[b] - (k - m);
+        if (p.draft_next_len != nullptr) p.draft_next_len[b] = (k > 0 && m == k) ? 2 : 1;
         if (p.out_tokens != nullptr) {
             int32_t *row = p.out_tokens + (size_t)b * (SPEC_K_MAX + 1);
             for (int i = 0; i <= SPEC_K_MAX; ++i)

@@ -50,12 +50,23 @@ class RejectArgs(C.Structure):
         ("accepted_len", C.c_void_p), ("next_token", C.c_void_p), ("out_tokens", C.c_void_p),
         ("counters", C.c_void_p), ("debug_u_ratio", C.c_void_p),
         ("accept_mode", C.c_int32),
+        ("kv_len", C.c_void_p), ("new_kv_len", C.c_void_p), ("draft_next_len", C.c_void_p),
+    ]
+
+
+class KvAppendArgs(C.Structure):
+    _fields_ = [
+        ("B", C.c_int32), ("Hkv", C.c_int32), ("d", C.c_int32), ("num_blocks", C.c_int32),
+        ("max_blocks_per_req", C.c_int32), ("T", C.c_int32), ("dtype", C.c_int32), ("kv_layout", C.c_int32),
+        ("new_k", C.c_void_p), ("new_v", C.c_void_p), ("k_cache", C.c_void_p), ("v_cache", C.c_void_p),
+        ("block_table", C.c_void_p), ("kv_len", C.c_void_p), ("cu_q_len", C.c_void_p),
+        ("host_kv_len", C.c_void_p), ("host_cu_q_len", C.c_void_p),
     ]
 
 
 EXPORTS = (
     "spec_verify_workspace_bytes", "spec_verify_attn", "spec_reject_sample", "spec_verify_step",
-    "spec_validate_attn", "spec_validate_reject", "spec_kv_repack_mfma", "spec_status_string",
+    "spec_validate_attn", "spec_validate_reject", "spec_kv_repack_mfma", "spec_kv_append", "spec_status_string",
     "spec_verify_version", "spec_profile_begin", "spec_profile_end",
     "spec_expected_generated_len", "spec_predict_latency", "spec_fit_latency",
     "spec_acceptance_update", "spec_acceptance_rate", "spec_argmax_goodput",
@@ -165,7 +176,7 @@ def make_attn_args(q, k_cache, v_cache, block_table, kv_len, cu_q_len, out, host
 
 def make_reject_args(target_logits, draft_logits, draft_tokens, cu_q_len, host_cu_q_len, accepted_len, next_token,
                      counters, *, philox_seed: int, philox_step: int, out_tokens=None, debug_u_ratio=None,
-                     accept_mode: int = 0):
+                     accept_mode: int = 0, kv_len=None, new_kv_len=None, draft_next_len=None):
     hc = _host_i32(host_cu_q_len)
     r = RejectArgs()
     r.B = hc.shape[0] - 1
@@ -183,8 +194,11 @@ def make_reject_args(target_logits, draft_logits, draft_tokens, cu_q_len, host_c
     r.counters = counters.data_ptr()
     r.debug_u_ratio = _dev_ptr(debug_u_ratio)
     r.accept_mode = accept_mode
+    r.kv_len = _dev_ptr(kv_len)
+    r.new_kv_len = _dev_ptr(new_kv_len)
+    r.draft_next_len = _dev_ptr(draft_next_len)
     return r, (hc, target_logits, draft_logits, draft_tokens, cu_q_len, accepted_len, next_token, counters,
-               out_tokens, debug_u_ratio)
+               out_tokens, debug_u_ratio, kv_len, new_kv_len, draft_next_len)
 
 
 def spec_verify_workspace_bytes(attn: Optional[AttnArgs], reject: Optional[RejectArgs]) -> int:
@@ -225,6 +239,27 @@ def spec_kv_repack_mfma(src_k, src_v, dst_k, dst_v, stream=None) -> None:
     assert bs == BLOCK_SIZE and src_k.element_size() == 2
     _check(lib().spec_kv_repack_mfma(src_k.data_ptr(), src_v.data_ptr(), dst_k.data_ptr(), dst_v.data_ptr(),
                                      nb, Hkv, d, _stream_handle(stream)), "spec_kv_repack_mfma")
+
+
+def spec_kv_append(new_k, new_v, k_cache, v_cache, block_table, kv_len, cu_q_len, host_kv_len, host_cu_q_len, *,
+                   kv_layout: int = KV_TOKEN_MAJOR, stream=None) -> None:
+    """Writes this step's K/V rows [T,Hkv,d] into the paged caches [nb,Hkv,16,d] in place."""
+    hk, hc = _host_i32(host_kv_len), _host_i32(host_cu_q_len)
+    a = KvAppendArgs()
+    a.T, a.Hkv, a.d = new_k.shape
+    a.B = hk.shape[0]
+    a.num_blocks = k_cache.shape[0]
+    a.max_blocks_per_req = block_table.shape[1]
+    a.dtype = SPEC_F32 if new_k.element_size() == 4 else SPEC_BF16
+    a.kv_layout = kv_layout
+    a.new_k, a.new_v = new_k.data_ptr(), new_v.data_ptr()
+    a.k_cache, a.v_cache = k_cache.data_ptr(), v_cache.data_ptr()
+    a.block_table, a.kv_len, a.cu_q_len = block_table.data_ptr(), kv_len.data_ptr(), cu_q_len.data_ptr()
+    a.host_kv_len, a.host_cu_q_len = hk.ctypes.data, hc.ctypes.data
+    fn = lib().spec_kv_append
+    fn.restype = C.c_int
+    fn.argtypes = [C.c_void_p, C.c_void_p]
+    _check(fn(C.addressof(a), _stream_handle(stream)), "spec_kv_append")
 
 
 def spec_profile_begin(max_launches: int) -> None:

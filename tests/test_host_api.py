@@ -183,3 +183,45 @@ def test_accept_mode_validation():
     # fewer logit rows get a statistics pass without a draft distribution: the workspace is smaller
     assert (sv.spec_verify_workspace_bytes(None, args(sv.ACCEPT_GREEDY, None))
             <= sv.spec_verify_workspace_bytes(None, args(sv.ACCEPT_SAMPLE, FAKE)))
+
+
+def test_kv_append_validation():
+    import ctypes as C
+    hk = np.array([20, 40], dtype=np.int32)
+    hc = np.array([0, 3, 5], dtype=np.int32)
+    FAKE = 0x1000
+    def args(**kw):
+        a = sv.KvAppendArgs()
+        a.B, a.Hkv, a.d, a.num_blocks, a.max_blocks_per_req, a.T = 2, 2, 128, 8, 3, 5
+        a.dtype, a.kv_layout = sv.SPEC_BF16, sv.KV_MFMA
+        for f in ("new_k", "new_v", "k_cache", "v_cache", "block_table", "kv_len", "cu_q_len"):
+            setattr(a, f, FAKE)
+        a.host_kv_len, a.host_cu_q_len = hk.ctypes.data, hc.ctypes.data
+        for k, v in kw.items():
+            setattr(a, k, v)
+        return a
+    fn = sv.lib().spec_kv_append
+    fn.restype = C.c_int
+    fn.argtypes = [C.c_void_p, C.c_void_p]
+    assert fn(None, None) == sv.SPEC_EINVAL
+    assert fn(C.addressof(args(new_k=None)), None) == sv.SPEC_EINVAL
+    assert fn(C.addressof(args(max_blocks_per_req=2)), None) == sv.SPEC_EINVAL     # 40 tokens need 3 pages
+    assert fn(C.addressof(args(dtype=sv.SPEC_F32)), None) == sv.SPEC_EUNSUPPORTED        # tiles are bf16 only
+    assert fn(C.addressof(args(d=96)), None) == sv.SPEC_EUNSUPPORTED
+    assert fn(C.addressof(args(T=6)), None) == sv.SPEC_EINVAL
+    bad_len = np.array([2, 40], dtype=np.int32)                                    # kv_len < q_len
+    assert fn(C.addressof(args(host_kv_len=bad_len.ctypes.data)), None) == sv.SPEC_EINVAL
+
+
+def test_bookkeeping_outputs_need_kv_len():
+    cu = np.array([0, 3, 5], dtype=np.int32)
+    FAKE = 0x1000
+    r = sv.RejectArgs()
+    r.B, r.V, r.T = 2, 64, 5
+    for f in ("target_logits", "draft_logits", "draft_tokens", "cu_q_len", "accepted_len", "next_token", "counters"):
+        setattr(r, f, FAKE)
+    r.host_cu_q_len = cu.ctypes.data
+    r.new_kv_len = FAKE
+    assert sv.spec_validate_reject(r) == sv.SPEC_EINVAL
+    r.kv_len = FAKE
+    assert sv.spec_validate_reject(r) == sv.SPEC_OK
