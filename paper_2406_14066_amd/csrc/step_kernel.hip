@@ -138,6 +138,16 @@ __device__ __forceinline__ void order_after_ticket()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
 }
 
+// Read-only inputs indexed by a block-uniform value (lengths, row offsets) are read through
+// the constant address space, which makes them scalar loads: they are served by the scalar
+// cache (these arrays are small and every block reads them) instead of a round trip to
+// the L2 under load, and they have a wait counter of their own.
+typedef const int32_t __attribute__((address_space(4))) *uniform_i32_ptr;
+__device__ __forceinline__ int uniform_load(const int32_t *base, int index)
+{
+    return ((uniform_i32_ptr)(uintptr_t)base)[__builtin_amdgcn_readfirstlane(index)];
+}
+
 // request that owns packed target row `row`: largest b with cu_q_len[b] <= row
 __device__ __forceinline__ int request_of_target_row(const int32_t *cu_q_len, int B, int row)
 {
@@ -434,8 +444,8 @@ __device__ __forceinline__ bool wait_all(int spin_limit, F probe)
 __device__ __forceinline__ bool accept_phase(const RejectParams &p, int b, RejectShared &sh, bool write_debug)
 {
     const int tid = threadIdx.x;
-    const int row_t0 = p.cu_q_len[b];
-    const int k = p.cu_q_len[b + 1] - row_t0 - 1;
+    const int row_t0 = uniform_load(p.cu_q_len, b);
+    const int k = uniform_load(p.cu_q_len, b + 1) - row_t0 - 1;
     const int row_d0 = row_t0 - b;
     const bool has_draft_rows = p.mode == SPEC_ACCEPT_SAMPLE;
     const int nrows = has_draft_rows ? 2 * k + 1 : k + 1;
@@ -525,11 +535,11 @@ __device__ __forceinline__ void stats_role(const RejectParams &p, int item, Reje
     const int nrec = 2 * p.T - p.B;
     int lo = (int)(((long long)rec * p.B) / nrec);
     if (lo > p.B - 1) lo = p.B - 1;
-    while (lo > 0 && 2 * p.cu_q_len[lo] - lo > rec) --lo;
-    while (lo < p.B - 1 && 2 * p.cu_q_len[lo + 1] - (lo + 1) <= rec) ++lo;
+    while (lo > 0 && 2 * uniform_load(p.cu_q_len, lo) - lo > rec) --lo;
+    while (lo < p.B - 1 && 2 * uniform_load(p.cu_q_len, lo + 1) - (lo + 1) <= rec) ++lo;
     const int b = lo;
-    const int row_t0 = p.cu_q_len[b];
-    const int k = p.cu_q_len[b + 1] - row_t0 - 1;
+    const int row_t0 = uniform_load(p.cu_q_len, b);
+    const int k = uniform_load(p.cu_q_len, b + 1) - row_t0 - 1;
     const int ri = rec - (2 * row_t0 - b);
     const int row = ri <= k ? row_t0 + ri : p.T + (row_t0 - b) + (ri - k - 1);
     stats_block(p, row, seg, sh);
@@ -546,8 +556,8 @@ struct RaceRows {
 __device__ __forceinline__ RaceRows race_rows(const RejectParams &p, int b, const RejectShared &sh)
 {
     RaceRows rr;
-    const int row_t0 = p.cu_q_len[b];
-    rr.k = p.cu_q_len[b + 1] - row_t0 - 1;
+    const int row_t0 = uniform_load(p.cu_q_len, b);
+    rr.k = uniform_load(p.cu_q_len, b + 1) - row_t0 - 1;
     rr.row_d0 = row_t0 - b;
     rr.m = sh.m;
     const double off_t_exact = -sh.lse2[rr.m];
@@ -604,8 +614,8 @@ __device__ __forceinline__ void race_role(const RejectParams &p, int item, Rejec
 __device__ __forceinline__ void greedy_final(const RejectParams &p, int b, RejectShared &sh)
 {
     const int tid = threadIdx.x;
-    const int row_t0 = p.cu_q_len[b];
-    const int k = p.cu_q_len[b + 1] - row_t0 - 1;
+    const int row_t0 = uniform_load(p.cu_q_len, b);
+    const int k = uniform_load(p.cu_q_len, b + 1) - row_t0 - 1;
     const int row_d0 = row_t0 - b;
     const int nstat = (k + 1) * p.stat_segments;
     const bool ok = wait_all(p.spin_limit, [&] {
@@ -712,7 +722,7 @@ __device__ __forceinline__ void final_role(const RejectParams &p, int b, RejectS
     info = (uint32_t)sh.m;
     __syncthreads();
     const int m = (int)(info & 0xFFu), k = (int)((info >> 8) & 0xFFu), near = (int)(info >> 16);
-    const int row_t0 = p.cu_q_len[b];
+    const int row_t0 = uniform_load(p.cu_q_len, b);
     const int row_d0 = row_t0 - b;
     if (!(win_score > 0.0f)) {
         // p - q has no positive entry (p == q to rounding): draw from p instead
@@ -801,13 +811,13 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
     int bt = 0;
     if (p.max_chunks == 1 && wave + kWaves * lane < p.max_blocks_per_req)
         bt = p.block_table[(size_t)b * p.max_blocks_per_req + wave + kWaves * lane];
-    const int L = p.kv_len[b];
+    const int L = uniform_load(p.kv_len, b);
     const int nchunks = (L + p.chunk_tokens - 1) / p.chunk_tokens;
     if (chunk >= nchunks) return;
     // even chunks per request, page aligned (never longer than chunk_tokens)
     const int C = ((L + nchunks - 1) / nchunks + SPEC_BLOCK_SIZE - 1) & ~(SPEC_BLOCK_SIZE - 1);
-    const int row0 = p.cu_q_len[b];
-    const int q_len = p.cu_q_len[b + 1] - row0;
+    const int row0 = uniform_load(p.cu_q_len, b);
+    const int q_len = uniform_load(p.cu_q_len, b + 1) - row0;
     const int group = p.Hq / p.Hkv;
     const int rows = q_len * group;
     const int tok0 = chunk * C;
