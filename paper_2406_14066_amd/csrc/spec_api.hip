@@ -137,10 +137,13 @@ AttnPlan plan_attn(const spec_attn_args *a)
     if (pl.use_mfma) {
         // One block per (request, KV head, chunk).  Splitting costs (partials, a merge, more
         // block start-ups), so the longest request is split only as far as needed to give every
-        // compute unit a block; two blocks with three row tiles, whose wavefronts spend a
-        // larger share of their time on arithmetic and need a second one beside them to keep
-        // loads in flight.
-        long target_blocks = (long)compute_units() * (pl.row_tiles >= 3 ? 2 : 1);
+        // compute unit a block.  With three row tiles the wavefronts spend a larger share of their
+        // time on arithmetic and need a second block beside them to keep loads in flight: then
+        // the target is two blocks per compute unit, less a sixteenth of the slots, which the
+        // rejection items flow through while the attention blocks (all resident from the start)
+        // stream.
+        const long cus = compute_units();
+        long target_blocks = pl.row_tiles >= 3 ? 2 * cus - cus / 8 : cus;
         if (const char *t = getenv("SPEC_VERIFY_TARGET_BLOCKS")) {   // tuning switch
             const long v = strtol(t, nullptr, 10);
             if (v >= 1 && v <= (1 << 20)) target_blocks = v;
@@ -245,7 +248,11 @@ AttnParams attn_params(const spec_attn_args *a, const AttnPlan &pl, char *ws)
         const double v = strtod(e, nullptr);
         if (v > 0.0 && v <= 1.0) p.reject_span = (float)v;
     }
-    p.attn_first_limit = compute_units();   // one attention block per compute unit leaves a slot beside it for the rejection items
+    p.attn_first_limit = 2 * compute_units();   // as many attention blocks as there are block slots: all start at once
+    if (const char *e = getenv("SPEC_VERIFY_ATTN_FIRST_LIMIT")) {   // tuning switch
+        const long v = strtol(e, nullptr, 10);
+        if (v >= 0 && v <= (1 << 20)) p.attn_first_limit = (int32_t)v;
+    }
     if (const char *e = getenv("SPEC_VERIFY_SPLIT_P")) p.split_p = (e[0] != '0');   // experiment switch
     return p;
 }

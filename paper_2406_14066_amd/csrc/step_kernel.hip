@@ -797,9 +797,15 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
     const int lane = tid & 63;
     const int n16 = lane & 15;
     const int g = lane >> 4;
-    const int chunk = item % p.max_chunks;
-    const int kvh = (item / p.max_chunks) % p.Hkv;
-    int b = item / p.max_chunks / p.Hkv;   // rank in the order of the attention items
+    // Items are chunk-major: all first chunks (requests longest first, KV heads innermost),
+    // then all second chunks, ...  Consecutive blocks go to different XCDs, so every XCD
+    // gets the same mix of chunk indices; the chunk indices that only the longest requests
+    // have come last (blocks of the others for these indices exit at once), instead of
+    // always falling on the same XCDs.
+    const int n_units = p.B * p.Hkv;
+    const int chunk = item / n_units;
+    const int kvh = (item % n_units) % p.Hkv;
+    int b = (item % n_units) / p.Hkv;   // rank in the order of the attention items
     if (order.n > 0) {
         const uint32_t pair = order.pairs[b >> 1];
         b = (int)((b & 1) ? pair >> 16 : pair & 0xFFFFu);
@@ -1066,48 +1072,66 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
     order_after_ticket();
 
     // Last chunk of this (request, KV head) to finish: merge all chunks in chunk order.
-    // Half a wavefront takes a query row (four head dims per lane); every load of a
-    // pass is issued before the first is used, so a pass costs one memory round trip.
+    // Half a wavefront takes two query rows at a time (four head dims per lane) and eight
+    // chunks of each per pass; every load of a pass is issued before the first is used, so
+    // a pass costs one memory round trip.
     constexpr int GROUP = 8;   // chunks merged per pass
+    constexpr int RB = NT >= 2 ? 2 : 1;   // rows in flight per half wavefront (one row tile: at most two passes anyway, and registers are tight)
     const int half = lane >> 5, l32 = lane & 31;
-    for (int r0 = 2 * wave; r0 < rows; r0 += 2 * kWaves) {
-        const int r = r0 + half;
-        const bool rv = r < rows;
-        const int rr = rv ? r : 0;
-        const size_t rh = (size_t)(row0 + rr / group) * p.Hq + kvh * group + rr % group;
-        const size_t base = rh * p.max_chunks;
-        const unsigned long long *ml = reinterpret_cast<const unsigned long long *>(p.ws_ml) + base;
-        const unsigned long long *pa =
-            reinterpret_cast<const unsigned long long *>(p.ws_acc) + base * (kD / 2) + 2 * l32;
-        float mx = kEmptyMax, denom = 0.0f;
-        f32x4 o = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int r0 = 2 * wave + half; r0 < rows; r0 += 2 * kWaves * RB) {
+        bool rv[RB];
+        size_t rh[RB];
+        const unsigned long long *ml[RB], *pa[RB];
+        float mx[RB], denom[RB];
+        f32x4 o[RB];
+#pragma unroll
+        for (int j = 0; j < RB; ++j) {
+            const int r = r0 + 2 * kWaves * j;
+            rv[j] = r < rows;
+            const int rr = rv[j] ? r : 0;
+            rh[j] = (size_t)(row0 + rr / group) * p.Hq + kvh * group + rr % group;
+            const size_t base = rh[j] * p.max_chunks;
+            ml[j] = reinterpret_cast<const unsigned long long *>(p.ws_ml) + base;
+            pa[j] = reinterpret_cast<const unsigned long long *>(p.ws_acc) + base * (kD / 2) + 2 * l32;
+            mx[j] = kEmptyMax;
+            denom[j] = 0.0f;
+            o[j] = (f32x4){0.0f, 0.0f, 0.0f, 0.0f};
+        }
         for (int c0 = 0; c0 < nchunks; c0 += GROUP) {
-            unsigned long long mlv[GROUP], a0[GROUP], a1[GROUP];
+            unsigned long long mlv[RB][GROUP], a0[RB][GROUP], a1[RB][GROUP];
 #pragma unroll
-            for (int c = 0; c < GROUP; ++c) {
-                const bool on = rv && c0 + c < nchunks;
-                mlv[c] = on ? fetch_u64(ml + c0 + c) : pack_f32x2(kEmptyMax, 0.0f);
-                a0[c] = on ? fetch_u64(pa + (size_t)(c0 + c) * (kD / 2)) : 0ull;
-                a1[c] = on ? fetch_u64(pa + (size_t)(c0 + c) * (kD / 2) + 1) : 0ull;
+            for (int j = 0; j < RB; ++j) {
+#pragma unroll
+                for (int c = 0; c < GROUP; ++c) {
+                    const bool on = rv[j] && c0 + c < nchunks;
+                    mlv[j][c] = on ? fetch_u64(ml[j] + c0 + c) : pack_f32x2(kEmptyMax, 0.0f);
+                    a0[j][c] = on ? fetch_u64(pa[j] + (size_t)(c0 + c) * (kD / 2)) : 0ull;
+                    a1[j][c] = on ? fetch_u64(pa[j] + (size_t)(c0 + c) * (kD / 2) + 1) : 0ull;
+                }
             }
-            float gmx = mx;
 #pragma unroll
-            for (int c = 0; c < GROUP; ++c) gmx = fmaxf(gmx, __uint_as_float((uint32_t)mlv[c]));
-            const float keep = fast_exp2(mx - gmx);   // rescale of what earlier passes summed
-            denom *= keep;
-            o *= keep;
-            mx = gmx;
+            for (int j = 0; j < RB; ++j) {
+                float gmx = mx[j];
 #pragma unroll
-            for (int c = 0; c < GROUP; ++c) {
-                const float w = fast_exp2(__uint_as_float((uint32_t)mlv[c]) - mx);
-                denom = fmaf(w, __uint_as_float((uint32_t)(mlv[c] >> 32)), denom);
-                o[0] = fmaf(w, __uint_as_float((uint32_t)a0[c]), o[0]);
-                o[1] = fmaf(w, __uint_as_float((uint32_t)(a0[c] >> 32)), o[1]);
-                o[2] = fmaf(w, __uint_as_float((uint32_t)a1[c]), o[2]);
-                o[3] = fmaf(w, __uint_as_float((uint32_t)(a1[c] >> 32)), o[3]);
+                for (int c = 0; c < GROUP; ++c) gmx = fmaxf(gmx, __uint_as_float((uint32_t)mlv[j][c]));
+                const float keep = fast_exp2(mx[j] - gmx);   // rescale of what earlier passes summed
+                denom[j] *= keep;
+                o[j] *= keep;
+                mx[j] = gmx;
+#pragma unroll
+                for (int c = 0; c < GROUP; ++c) {
+                    const float w = fast_exp2(__uint_as_float((uint32_t)mlv[j][c]) - gmx);
+                    denom[j] = fmaf(w, __uint_as_float((uint32_t)(mlv[j][c] >> 32)), denom[j]);
+                    o[j][0] = fmaf(w, __uint_as_float((uint32_t)a0[j][c]), o[j][0]);
+                    o[j][1] = fmaf(w, __uint_as_float((uint32_t)(a0[j][c] >> 32)), o[j][1]);
+                    o[j][2] = fmaf(w, __uint_as_float((uint32_t)a1[j][c]), o[j][2]);
+                    o[j][3] = fmaf(w, __uint_as_float((uint32_t)(a1[j][c] >> 32)), o[j][3]);
+                }
             }
         }
-        if (rv) *reinterpret_cast<f32x4 *>(p.out + rh * kD + 4 * l32) = o * (1.0f / denom);
+#pragma unroll
+        for (int j = 0; j < RB; ++j)
+            if (rv[j]) *reinterpret_cast<f32x4 *>(p.out + rh[j] * kD + 4 * l32) = o[j] * (1.0f / denom[j]);
     }
 }
 
