@@ -211,9 +211,9 @@ struct RejectShared {
 // The running offset is integer-valued in base-2 units, so every rescale is an
 // exact power of two and x*log2(e) - offset is rounded once (log2 e enters as an
 // fp32 hi/lo pair inside fused multiply-adds).
+template <int UNROLL>   // vectors of 16 bytes in flight per thread (these blocks share the attention role's register budget)
 __device__ __forceinline__ void stats_block(const RejectParams &p, int row, int seg, RejectShared &sh)
 {
-    constexpr int UNROLL = 16;   // 256 bytes per thread in flight (these blocks share the attention role's register budget)
     const int tid = threadIdx.x;
     const float *base = row < p.T ? p.target_logits + (size_t)row * p.V
                                   : p.draft_logits + (size_t)(row - p.T) * p.V;
@@ -520,13 +520,14 @@ __device__ __forceinline__ bool accept_phase(const RejectParams &p, int b, Rejec
 // Statistics items are ordered by request (its target rows, then its draft rows), so that
 // the first requests' statistics are complete early and their races can start while
 // later requests' rows are still being read.
+template <int UNROLL>
 __device__ __forceinline__ void stats_role(const RejectParams &p, int item, RejectShared &sh)
 {
     const int rec = item / p.stat_segments;          // (request, row of the request)
     const int seg = item - rec * p.stat_segments;
     if (p.mode != SPEC_ACCEPT_SAMPLE) {   // target rows only: rec is the row
         if (p.mode == SPEC_ACCEPT_GREEDY) argmax_block(p, rec, seg, sh);
-        else stats_block(p, rec, seg, sh);
+        else stats_block<UNROLL>(p, rec, seg, sh);
         return;
     }
     // largest b with 2 * cu_q_len[b] - b <= rec (rows of the requests before b).  Start from
@@ -542,7 +543,7 @@ __device__ __forceinline__ void stats_role(const RejectParams &p, int item, Reje
     const int k = uniform_load(p.cu_q_len, b + 1) - row_t0 - 1;
     const int ri = rec - (2 * row_t0 - b);
     const int row = ri <= k ? row_t0 + ri : p.T + (row_t0 - b) + (ri - k - 1);
-    stats_block(p, row, seg, sh);
+    stats_block<UNROLL>(p, row, seg, sh);
 }
 
 // Offsets of the race rows of request b after accept_phase.
@@ -1201,7 +1202,8 @@ __global__ __launch_bounds__(kThreads, 2) void spec_step_kernel(StepArgs args)
         if (!is_attn) {
             __shared__ RejectShared rsh;
             if (item < gs.n_stat) {
-                stats_role(rp, item, rsh);
+                // a whole 32000-entry row per round trip where the registers allow it
+                stats_role<(HAS_ATTN && NT >= 2) ? 32 : 16>(rp, item, rsh);
             } else {
                 const int after = item - gs.n_stat;
                 const int n_race = rp.B * rp.race_segments;
