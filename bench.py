@@ -217,24 +217,31 @@ def main():
 
     if not args.no_cpu_baseline:
         import oracle
-        t2 = time.perf_counter()
-        oracle.verify_attn(w.q, w.k_pages, w.v_pages, w.block_table, w.kv_len, w.cu_q_len)
-        t3 = time.perf_counter()
-        if mode == sv.ACCEPT_SAMPLE:
-            oracle.reject_sample(w.target_logits, w.draft_logits, w.draft_tokens, w.cu_q_len, w.philox_seed,
-                                 w.philox_step)
-        elif mode == sv.ACCEPT_GREEDY:
-            oracle.reject_greedy(w.target_logits, w.draft_tokens, w.cu_q_len)
-        else:
-            oracle.reject_onehot(w.target_logits, w.draft_tokens, w.cu_q_len, w.philox_seed, w.philox_step)
-        t4 = time.perf_counter()
+        # the oracle as it stands, single thread, on whole steps of this workload until about
+        # ten seconds have passed (at least one step)
+        reps, t_attn, t_rej = 0, 0.0, 0.0
+        while reps == 0 or (t_attn + t_rej < 10.0 and reps < 1000):
+            t2 = time.perf_counter()
+            oracle.verify_attn(w.q, w.k_pages, w.v_pages, w.block_table, w.kv_len, w.cu_q_len)
+            t3 = time.perf_counter()
+            if mode == sv.ACCEPT_SAMPLE:
+                oracle.reject_sample(w.target_logits, w.draft_logits, w.draft_tokens, w.cu_q_len, w.philox_seed,
+                                     w.philox_step)
+            elif mode == sv.ACCEPT_GREEDY:
+                oracle.reject_greedy(w.target_logits, w.draft_tokens, w.cu_q_len)
+            else:
+                oracle.reject_onehot(w.target_logits, w.draft_tokens, w.cu_q_len, w.philox_seed, w.philox_step)
+            t4 = time.perf_counter()
+            t_attn += t3 - t2
+            t_rej += t4 - t3
+            reps += 1
         out["cpu_baseline"] = {
-            "value": w.verified_tokens() / (t4 - t2),
+            "value": reps * w.verified_tokens() / (t_attn + t_rej),
             "unit": "tokens/s",
             "cores": 1,
             "kind": "oracle",
-            "sample": "the whole %s step once (attention %.2f s + rejection sampling %.2f s), single thread; host has %d cpus"
-                      % (w.name, t3 - t2, t4 - t3, os.cpu_count()),
+            "sample": "the whole %s step %d times (attention %.2f s + rejection sampling %.2f s per step), single thread; host has %d cpus"
+                      % (w.name, reps, t_attn / reps, t_rej / reps, os.cpu_count()),
         }
     print(json.dumps(out))
 
