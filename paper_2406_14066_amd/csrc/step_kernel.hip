@@ -15,24 +15,25 @@
 //   attention    one (request, KV head, KV chunk) each; the block that completes
 //                the LAST chunk of a (request, KV head) merges the chunk partials
 //                and writes the output.
-// The rejection items keep that order among themselves and are spread evenly among
-// the attention items (see GridSplit), so that the rejection half, whose stages
-// depend on each other, runs underneath the long attention stream.
+// Other acceptance rules reuse the stages: greedy acceptance computes (largest logit,
+// lowest id) per (target row, segment) in the statistics stage and has no race; a
+// point-mass draft needs statistics of the target rows only and leaves the rejected
+// token out of the race.
+// The rejection items keep that order among themselves and are mixed into the first part
+// of the attention items (see GridSplit), so that the rejection half, whose stages depend
+// on each other, runs underneath the attention stream and is done before it.
 //
 // Attention blocks never wait: "last one out merges" is decided with one atomic
 // ticket per (request, KV head).  Race and final items consume what earlier items
-// of the grid published (tagged with the call's generation); by their place at
-// later in the grid the producers were scheduled before them, and the bounded wait
-// that checks for the data can only end early, never hang: the producers precede
-// the consumers in dispatch order and wait for nothing.  (Same-address atomic tickets
-// cost about 0.3 us per arrival here, so they are kept for the attention chunks,
-// which arrive spread out in time, and avoided for the hundreds of statistics
-// blocks of a request, which arrive together.)  Tickets
-// carry the call's generation tag in their high half, so a workspace needs no
-// zero-initialisation and a call that never finished cannot poison the next;
-// the last arrival also resets its ticket, so a replayed HIP graph (same tag)
-// works too.  The rejection half is small and sits first in the grid: it runs
-// while the attention half streams the KV cache, and both are bound by HBM.
+// of the grid published (tagged with the call's generation).  The producers precede
+// the consumers in the grid, so they were dispatched before them, and they wait for
+// nothing: the bounded wait that checks for the data always ends.  (Same-address atomic
+// tickets cost about 0.3 us per arrival here, so they are kept for the attention chunks,
+// which arrive spread out in time, and avoided for the hundreds of statistics blocks of a
+// request, which arrive together.)  Tickets and records carry the call's generation tag
+// in their high half, so a workspace needs no zero-initialisation and a call that never
+// finished cannot poison the next; the last user also resets them, so a replayed HIP
+// graph (same tag) works too.
 //
 // Attention arithmetic, per 16-token page and 16-row tile (lane = 16*g + n):
 //   S^T[token][row] = K[token][:] . Q[row][:]        4 x v_mfma_f32_16x16x32_bf16
@@ -1139,18 +1140,23 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
 // ===========================================================================
 // The kernel
 // ===========================================================================
-// Grid order.  The rejection items always keep their own order (statistics, race, final).
-//  - Few, long attention blocks (no more than fit on the device at once): attention
-//    first.  The hardware dispatcher then spreads them evenly over the compute units
-//    (two of them on one unit would take twice as long as the rest), and the
-//    rejection items fill the block slots that are left.
-//  - Many attention blocks: the rejection items are spread evenly among them, so that
-//    at any time only a fraction of the resident blocks belongs to the latency-bound
-//    rejection stages and the rest keep streaming the KV cache.  The mixing is done per
-//    row of 8 consecutive blocks: the hardware deals consecutive blocks to the 8 XCDs in
-//    turn, and a finer pattern would alias with that (with equal counts, "every other
-//    block" would put all attention on four XCDs and all rejection on the other four).
-//    Row r is an attention row iff floor((r+1) * rows_attn / rows) > floor(r * rows_attn / rows).
+// Grid order.  The hardware dispatcher places blocks strictly in grid order and waits for
+// the slot it has chosen, so block slots sit idle when neighbouring blocks run for very
+// different times.  The order keeps neighbours alike and ends on independent work.
+// The rejection items always keep their own order (statistics, race, final).
+//  - No more attention blocks than block slots: attention first.  All of them are
+//    resident from the start (one per compute unit if there are few: two on one unit
+//    would take twice as long as the rest), and the rejection items flow through the
+//    slots that are left.
+//  - More attention blocks: they take the requests longest first (so blocks that run at
+//    the same time take about equally long), and the rejection items are mixed into the
+//    first part of them (reject_span of the attention rows), so that the dependent
+//    rejection stages are done before the attention items are and the tail of the launch
+//    is short attention blocks.  The mixing is done per row of 8 consecutive blocks: the
+//    hardware deals consecutive blocks to the 8 XCDs in turn, and a finer pattern would
+//    alias with that (with equal counts, "every other block" would put all attention on
+//    four XCDs and all rejection on the other four).  Within the mixed part, row r is an
+//    attention row iff floor((r+1) * rows_attn / rows) > floor(r * rows_attn / rows).
 constexpr int kXcds = 8;
 
 struct GridSplit {
