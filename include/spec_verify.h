@@ -217,11 +217,13 @@ spec_status spec_kv_repack_mfma(const void *src_k, const void *src_v, void *dst_
 /*
  * Measurement aid (not part of the step): per-kernel GPU time from HIP events.
  * Between spec_profile_begin and spec_profile_end every kernel the library
- * launches (up to max_launches of them) is bracketed by two event records on
- * the launch stream.  spec_profile_end waits for those events and returns, per
- * kernel id, the summed duration in milliseconds and the number of launches
- * (both arrays have SPEC_NUM_KERNELS entries).  begin creates the events, so
- * it must not be called during stream capture; the pair is not thread safe.
+ * launches (up to max_launches of them) gets a pair of events: the step kernel
+ * carries them itself (they receive the time stamps of the launch's own begin
+ * and end), the other kernels are bracketed by two event records on the launch
+ * stream.  spec_profile_end waits for those events and returns, per kernel id,
+ * the summed duration in milliseconds and the number of launches (both arrays
+ * have SPEC_NUM_KERNELS entries).  begin creates the events, so it must not be
+ * called during stream capture; the pair is not thread safe.
  */
 #define SPEC_NUM_KERNELS 5
 #define SPEC_KERNEL_STEP 0          /* the whole step in one launch (attention + rejection sampling) */

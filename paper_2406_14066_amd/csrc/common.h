@@ -105,10 +105,17 @@ struct UnitOrder {
     alignas(4) uint16_t request[kMaxOrdered];
 };
 
+// Events that receive the begin and end time stamps of a kernel launch itself (both null:
+// none).  Unlike event records placed before and after the launch on the stream they do
+// not include the time the stream spends on the records.
+struct LaunchEvents {
+    hipEvent_t start, stop;
+};
+
 // One launch for the whole step (either half may be absent).  `attn` needs the
 // matrix-instruction path (bf16, SPEC_KV_MFMA, d = 128, row_tiles <= 3).  `order` may be null.
 hipError_t launch_step_fused(const AttnParams *attn, int row_tiles, const RejectParams *reject, const UnitOrder *order,
-                             hipStream_t stream);
+                             LaunchEvents events, hipStream_t stream);
 
 // Generic attention path: partial kernel + combine kernel.
 hipError_t launch_attn_generic(const AttnParams &p, int dtype, hipStream_t stream);

@@ -41,6 +41,19 @@ hipError_t timed(int kernel_id, hipStream_t stream, F launch)
     if (rec) (void)hipEventRecord(g_prof.events[2 * pair + 1], stream);
     return err;
 }
+// The same for a launch that can carry its events itself.
+template <typename F>
+hipError_t timed_launch(int kernel_id, F launch)
+{
+    LaunchEvents ev = {nullptr, nullptr};
+    if (g_prof.on && g_prof.kernel_of_pair.size() < g_prof.capacity_pairs) {
+        const size_t pair = g_prof.kernel_of_pair.size();
+        g_prof.kernel_of_pair.push_back(kernel_id);
+        ev.start = g_prof.events[2 * pair];
+        ev.stop = g_prof.events[2 * pair + 1];
+    }
+    return launch(ev);
+}
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 spec_status validate_attn(const spec_attn_args *a)
@@ -350,8 +363,9 @@ spec_status spec_verify_attn(const spec_attn_args *attn, void *workspace, size_t
     if (!pl.use_mfma) return run_attn_generic(ap, attn->qkv_dtype, stream);
     UnitOrder order_table;
     const UnitOrder *order = make_order(attn, order_table);
-    hipError_t err = timed(SPEC_KERNEL_ATTN, stream,
-                           [&] { return launch_step_fused(&ap, pl.row_tiles, nullptr, order, stream); });
+    hipError_t err = timed_launch(SPEC_KERNEL_ATTN, [&](LaunchEvents ev) {
+        return launch_step_fused(&ap, pl.row_tiles, nullptr, order, ev, stream);
+    });
     if (err == hipSuccess && !pl.fused_combine && pl.max_chunks > 1)
         err = timed(SPEC_KERNEL_ATTN_COMBINE, stream, [&] { return launch_attn_combine(ap, stream); });
     return err == hipSuccess ? SPEC_OK : SPEC_EHIP;
@@ -368,7 +382,7 @@ spec_status spec_reject_sample(const spec_reject_args *reject, void *workspace, 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const RejectParams rp = reject_params(reject, pl, static_cast<char *>(workspace));
     const hipError_t err =
-        timed(SPEC_KERNEL_REJECT, stream, [&] { return launch_step_fused(nullptr, 0, &rp, nullptr, stream); });
+        timed_launch(SPEC_KERNEL_REJECT, [&](LaunchEvents ev) { return launch_step_fused(nullptr, 0, &rp, nullptr, ev, stream); });
     return err == hipSuccess ? SPEC_OK : SPEC_EHIP;
 }
 
@@ -391,8 +405,9 @@ spec_status spec_verify_step(const spec_attn_args *attn, const spec_reject_args 
         // the whole step in one launch
         UnitOrder order_table;
         const UnitOrder *order = make_order(attn, order_table);
-        hipError_t err = timed(SPEC_KERNEL_STEP, stream,
-                               [&] { return launch_step_fused(&ap, apl.row_tiles, &rp, order, stream); });
+        hipError_t err = timed_launch(SPEC_KERNEL_STEP, [&](LaunchEvents ev) {
+            return launch_step_fused(&ap, apl.row_tiles, &rp, order, ev, stream);
+        });
         if (err == hipSuccess && !apl.fused_combine && apl.max_chunks > 1)
             err = timed(SPEC_KERNEL_ATTN_COMBINE, stream, [&] { return launch_attn_combine(ap, stream); });
         return err == hipSuccess ? SPEC_OK : SPEC_EHIP;
@@ -400,7 +415,7 @@ spec_status spec_verify_step(const spec_attn_args *attn, const spec_reject_args 
     st = run_attn_generic(ap, attn->qkv_dtype, stream);
     if (st != SPEC_OK) return st;
     const hipError_t err =
-        timed(SPEC_KERNEL_REJECT, stream, [&] { return launch_step_fused(nullptr, 0, &rp, nullptr, stream); });
+        timed_launch(SPEC_KERNEL_REJECT, [&](LaunchEvents ev) { return launch_step_fused(nullptr, 0, &rp, nullptr, ev, stream); });
     return err == hipSuccess ? SPEC_OK : SPEC_EHIP;
 }
 

@@ -48,6 +48,8 @@
 // with u) is fp64.
 #include "common.h"
 
+#include <hip/hip_ext.h>
+
 #include <float.h>
 #include <math.h>
 #include <stddef.h>
@@ -1231,7 +1233,7 @@ __global__ __launch_bounds__(kThreads, 2) void spec_step_kernel(StepArgs args)
 
 template <int NT, bool HAS_ATTN, bool HAS_REJECT>
 hipError_t launch(const AttnParams &ap, const RejectParams &rp, int n_stat, int n_attn, int n_race,
-                  const UnitOrder *order, hipStream_t stream)
+                  const UnitOrder *order, LaunchEvents ev, hipStream_t stream)
 {
     StepArgs args;
     args.ap = ap;
@@ -1255,17 +1257,27 @@ hipError_t launch(const AttnParams &ap, const RejectParams &rp, int n_stat, int 
     if (gs.rows_attn_mixed < 1) gs.rows_attn_mixed = 1;
     if (gs.rows_attn_mixed > rows_attn_all) gs.rows_attn_mixed = rows_attn_all;
     const dim3 grid(mixed ? ((n_attn + kXcds - 1) / kXcds + (n_reject + kXcds - 1) / kXcds) * kXcds : n_reject + n_attn);
-    if (HAS_ATTN && !ap.split_p)
-        hipLaunchKernelGGL((spec_step_kernel<NT, HAS_ATTN, HAS_REJECT, false>), grid, dim3(kThreads), 0, stream, args);
-    else
-        hipLaunchKernelGGL((spec_step_kernel<NT, HAS_ATTN, HAS_REJECT, true>), grid, dim3(kThreads), 0, stream, args);
+    // (with events the extended launch attaches them to the kernel's own begin and end)
+    if (HAS_ATTN && !ap.split_p) {
+        if (ev.start != nullptr)
+            hipExtLaunchKernelGGL((spec_step_kernel<NT, HAS_ATTN, HAS_REJECT, false>), grid, dim3(kThreads), 0, stream,
+                                  ev.start, ev.stop, 0, args);
+        else
+            hipLaunchKernelGGL((spec_step_kernel<NT, HAS_ATTN, HAS_REJECT, false>), grid, dim3(kThreads), 0, stream, args);
+    } else {
+        if (ev.start != nullptr)
+            hipExtLaunchKernelGGL((spec_step_kernel<NT, HAS_ATTN, HAS_REJECT, true>), grid, dim3(kThreads), 0, stream,
+                                  ev.start, ev.stop, 0, args);
+        else
+            hipLaunchKernelGGL((spec_step_kernel<NT, HAS_ATTN, HAS_REJECT, true>), grid, dim3(kThreads), 0, stream, args);
+    }
     return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_step_fused(const AttnParams *attn, int row_tiles, const RejectParams *reject, const UnitOrder *order,
-                              hipStream_t stream)
+                             LaunchEvents ev, hipStream_t stream)
 {
     AttnParams ap = {};
     RejectParams rp = {};
@@ -1285,18 +1297,18 @@ hipError_t launch_step_fused(const AttnParams *attn, int row_tiles, const Reject
             return hipErrorInvalidValue;
         n_attn = ap.B * ap.Hkv * ap.max_chunks;
     }
-    if (attn == nullptr) return launch<1, false, true>(ap, rp, n_stat, 0, n_race, nullptr, stream);
+    if (attn == nullptr) return launch<1, false, true>(ap, rp, n_stat, 0, n_race, nullptr, ev, stream);
     if (reject == nullptr) {
         switch (row_tiles) {
-            case 1: return launch<1, true, false>(ap, rp, 0, n_attn, 0, order, stream);
-            case 2: return launch<2, true, false>(ap, rp, 0, n_attn, 0, order, stream);
-            default: return launch<3, true, false>(ap, rp, 0, n_attn, 0, order, stream);
+            case 1: return launch<1, true, false>(ap, rp, 0, n_attn, 0, order, ev, stream);
+            case 2: return launch<2, true, false>(ap, rp, 0, n_attn, 0, order, ev, stream);
+            default: return launch<3, true, false>(ap, rp, 0, n_attn, 0, order, ev, stream);
         }
     }
     switch (row_tiles) {
-        case 1: return launch<1, true, true>(ap, rp, n_stat, n_attn, n_race, order, stream);
-        case 2: return launch<2, true, true>(ap, rp, n_stat, n_attn, n_race, order, stream);
-        default: return launch<3, true, true>(ap, rp, n_stat, n_attn, n_race, order, stream);
+        case 1: return launch<1, true, true>(ap, rp, n_stat, n_attn, n_race, order, ev, stream);
+        case 2: return launch<2, true, true>(ap, rp, n_stat, n_attn, n_race, order, ev, stream);
+        default: return launch<3, true, true>(ap, rp, n_stat, n_attn, n_race, order, ev, stream);
     }
 }
 
