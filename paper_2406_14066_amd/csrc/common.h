@@ -41,23 +41,27 @@ struct AttnPlan {
 };
 
 struct AttnParams {
+    // (scalars first and in pairs of 4-byte fields, so that the struct has no padding holes:
+    // a hole next to a pointer made the compiler keep a private-memory copy of that slice)
     int32_t B, Hq, Hkv, d, num_blocks, max_blocks_per_req, T;
     int32_t kv_layout;
     int32_t chunk_tokens, max_chunks;
     float scale_log2;  // softmax scale times log2(e): scores are kept in base-2 units
-    const void *q, *k_cache, *v_cache;
-    const int32_t *block_table, *kv_len, *cu_q_len;
-    float *out;
-    float *ws_acc;
-    float *ws_ml;
-    unsigned long long *tickets;
     uint32_t generation;  // tags this call's ticket values, never 0
     int32_t fused_combine;        // matrix kernel: the last chunk's block merges the partials (needs max_chunks <= kMaxFusedChunks)
     int32_t attn_first_limit;     // attention blocks go first in the grid when there are at most this many
     float reject_span;            // fraction of the attention items among which the rejection items are spread in the grid
     int32_t split_p;              // feed the softmax weights to the PV product as bf16 high + low parts
     int32_t single_chunk_direct;  // requests with one chunk were written straight to `out`: the combine kernel skips them
+    int32_t reserved;
+    const void *q, *k_cache, *v_cache;
+    const int32_t *block_table, *kv_len, *cu_q_len;
+    float *out;
+    float *ws_acc;
+    float *ws_ml;
+    unsigned long long *tickets;
 };
+static_assert(sizeof(AttnParams) == 18 * 4 + 10 * 8, "AttnParams has padding");
 
 // ---------------------------------------------------------------- rejection
 // Records handed between the rejection stages are arrays of 8-byte words, each a
@@ -78,24 +82,26 @@ struct RejectPlan {
 };
 
 struct RejectParams {
+    // (4-byte scalars first, an even number of them: no padding holes, see AttnParams)
     int32_t B, V, T;
     int32_t mode;   // spec_accept_mode
+    uint32_t seed_lo, seed_hi, step_lo, step_hi24;
+    int32_t stat_segments, stat_seg_len;
+    int32_t race_segments, race_seg_len;
+    int32_t spin_limit;                  // polls a consumer block spends waiting for its producers
+    uint32_t generation;
     const float *target_logits, *draft_logits;
     const int32_t *draft_tokens, *cu_q_len;
-    uint32_t seed_lo, seed_hi, step_lo, step_hi24;
     int32_t *accepted_len, *next_token, *out_tokens;
     unsigned long long *counters;
     double *debug_u_ratio;
     const int32_t *kv_len;               // cache bookkeeping after acceptance (optional)
     int32_t *new_kv_len, *draft_next_len;
-    int32_t stat_segments, stat_seg_len;
-    int32_t race_segments, race_seg_len;
-    int32_t spin_limit;                  // polls a race block spends waiting for its request's accept phase
     unsigned long long *stats;           // [rows][stat_segments][3]
     unsigned long long *race_partial;    // [B][race_segments][2]
     unsigned long long *race_info;       // [B]
-    uint32_t generation;
 };
+static_assert(sizeof(RejectParams) == 14 * 4 + 15 * 8, "RejectParams has padding");
 
 // Order in which the attention items take the requests (longest first), passed as a
 // kernel argument.  n == 0: the given order.
