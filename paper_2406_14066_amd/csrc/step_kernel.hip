@@ -64,6 +64,11 @@ constexpr int kWaves = kThreads / kWave;
 constexpr int kD = 128;
 constexpr int kPageHeadBytes = SPEC_BLOCK_SIZE * kD * 2;  // 4096
 constexpr int kBufferFlags = 0x00020000;   // raw 32-bit buffer descriptor, word 3
+// Cache policy of the loads that stream data read once (KV pages, the race's logit rows):
+// non-temporal, i.e. the lines are first in line for replacement in the L2.  Without it the
+// stream pushes out what the blocks do come back to (code, block tables, queries, hand-off
+// words); measured on the four large workloads the hint alone takes 8-10% off the step.
+constexpr int kStreamPolicy = 2;           // "nt" bit of a raw buffer load
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
@@ -73,6 +78,13 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// 16 bytes of logits that this launch will not read again (see kStreamPolicy).
+__device__ __forceinline__ float4 load_streaming(const float *p)
+{
+    const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(p));
+    return make_float4(v[0], v[1], v[2], v[3]);
+}
 
 // ---------------------------------------------------------------------------
 // Tickets.  Word = generation << 32 | arrivals.  Returns how many blocks arrived
@@ -370,8 +382,8 @@ __device__ __forceinline__ void race_segment(const RejectParams &p, const float 
         for (int u = 0; u < U; ++u) {
             const int g = g0 + u * kThreads;
             const float4 ninf = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
-            xt[u] = g < g_end ? *reinterpret_cast<const float4 *>(target_row + 4 * g) : ninf;
-            xd[u] = (draft_row != nullptr && g < g_end) ? *reinterpret_cast<const float4 *>(draft_row + 4 * g) : ninf;
+            xt[u] = g < g_end ? load_streaming(target_row + 4 * g) : ninf;
+            xd[u] = (draft_row != nullptr && g < g_end) ? load_streaming(draft_row + 4 * g) : ninf;
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -775,9 +787,21 @@ struct PageRegs {
     u32x4 v[4];  // v[pp]: dims 32*pp + n (low half) and 32*pp + 16 + n (high half), tokens 4g .. 4g+3
 };
 
+// The query rows and the output tile pass through LDS so that global memory sees them as
+// whole rows (full cache lines, each once per block) instead of the 64-byte pieces of the
+// matrix-operand layout, once per wavefront: with 32 to 48 query rows per KV head (grouped
+// heads) these requests were a fifth of all the block's memory requests, and the launch is
+// bound by requests as much as by bytes.  Rows are padded against bank conflicts.
+constexpr int kQStride = kD * 2 + 16;   // bytes per bf16 query row in LDS
+constexpr int kOStride = kD * 4 + 16;   // bytes per fp32 output row in LDS
+
 template <int NT>
 struct AttnShared {
-    f32x4 acc[2][NT][8][kWave];
+    union {
+        f32x4 acc[2][NT][8][kWave];               // epilogue: partial results of wavefronts 2, 3, then 1
+        unsigned char q[NT * 16 * kQStride];      // prologue: the block's query rows
+        unsigned char o[NT * 16 * kOStride];      // epilogue of an unsplit request: the output tile
+    };
     float m[2][NT][kWave];
     float l[2][NT][kWave];
     int last;
@@ -839,9 +863,21 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
     if (p.max_chunks != 1 && wave + kWaves * lane < npages)
         bt = p.block_table[(size_t)b * p.max_blocks_per_req + page0 + wave + kWaves * lane];
 
-    // Q as the B operand of S^T = K Q^T, and each lane's last visible key
-    bf16x8 qreg[NT][4];
-    int limit[NT];
+    // Q: the block fetches its query rows once, 16 bytes per thread and consecutive threads
+    // along a row (the heads of a group are adjacent in memory), and leaves them in LDS
+    u32x4 qpiece[NT];
+#pragma unroll
+    for (int i = 0; i < NT; ++i) {
+        const int piece = tid + i * kThreads;   // 16 pieces per row
+        const int r = piece >> 4, c = piece & 15;
+        qpiece[i] = (u32x4){0u, 0u, 0u, 0u};
+        if (r < rows) {
+            const size_t rh = (size_t)(row0 + r / group) * p.Hq + kvh * group + r % group;
+            qpiece[i] = *reinterpret_cast<const u32x4 *>(static_cast<const char *>(p.q) + rh * (kD * 2) + c * 16);
+        }
+    }
+    bf16x8 qreg[NT][4];   // filled from LDS below
+    int limit[NT];     // each lane's last visible key
     int out_row[NT];   // packed (token row * Hq + head) of this lane's query row, -1 if padding
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
@@ -849,15 +885,8 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
         const bool valid = r < rows;
         const int j = valid ? r / group : 0;
         const int gq = valid ? r % group : 0;
-        const size_t rh = (size_t)(row0 + j) * p.Hq + kvh * group + gq;
-        const __bf16 *qp = static_cast<const __bf16 *>(p.q) + rh * kD + g * 8;
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-            qreg[nt][kk] = valid ? *reinterpret_cast<const bf16x8 *>(qp + kk * 32) : z;
-        }
         limit[nt] = valid ? L - q_len + j : -1;
-        out_row[nt] = valid ? (int)rh : -1;
+        out_row[nt] = valid ? (int)((size_t)(row0 + j) * p.Hq + kvh * group + gq) : -1;
     }
 
     // Pages are read with buffer loads through a descriptor that covers exactly one
@@ -881,9 +910,9 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
         const __amdgpu_buffer_rsrc_t vd = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<char *>(vhead + (size_t)page * page_stride), 0, bytes, kBufferFlags);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) r.k[i] = __builtin_amdgcn_raw_buffer_load_b128(kd, lane_off, i * 1024, 0);
+        for (int i = 0; i < 4; ++i) r.k[i] = __builtin_amdgcn_raw_buffer_load_b128(kd, lane_off, i * 1024, kStreamPolicy);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) r.v[i] = __builtin_amdgcn_raw_buffer_load_b128(vd, lane_off, i * 1024, 0);
+        for (int i = 0; i < 4; ++i) r.v[i] = __builtin_amdgcn_raw_buffer_load_b128(vd, lane_off, i * 1024, kStreamPolicy);
     };
 
     f32x4 acc[NT][8];
@@ -982,6 +1011,22 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
             if (it + j < my_pages) consume(r[j], wave + kWaves * (it + j));
     };
     load_batch(0, batch_a);
+
+    // Q as the B operand of S^T = K Q^T, out of LDS (the first pages are on their way)
+#pragma unroll
+    for (int i = 0; i < NT; ++i) {
+        const int piece = tid + i * kThreads;
+        *reinterpret_cast<u32x4 *>(sh.q + (piece >> 4) * kQStride + (piece & 15) * 16) = qpiece[i];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+            qreg[nt][kk] = *reinterpret_cast<const bf16x8 *>(sh.q + (nt * 16 + n16) * kQStride + kk * 64 + g * 16);
+    }
+    __syncthreads();   // the epilogue reuses this memory
+
     for (int it0 = 0; it0 < my_pages; it0 += 2 * P) {
         arrived(batch_a);
         load_batch(it0 + P, batch_b);
@@ -1030,16 +1075,25 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
     __syncthreads();
 
     if (nchunks == 1) {
-        // the only chunk of this (request, KV head): normalise and write the output
-        if (wave != 0) return;
-        merge(0);
+        // the only chunk of this (request, KV head): normalise, lay the tile out by rows in
+        // LDS, and let the whole block write the rows (16 bytes per thread, consecutive
+        // threads along a row)
+        if (wave == 0) {
+            merge(0);   // (its reads of the shared partials precede the writes below in program order)
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            if (out_row[nt] < 0) continue;
-            const float inv = 1.0f / l_run[nt];
-            float *dst = p.out + (size_t)out_row[nt] * kD + 4 * g;
+            for (int nt = 0; nt < NT; ++nt) {
+                const float inv = 1.0f / l_run[nt];
 #pragma unroll
-            for (int mt = 0; mt < 8; ++mt) *reinterpret_cast<f32x4 *>(dst + 16 * mt) = acc[nt][mt] * inv;
+                for (int mt = 0; mt < 8; ++mt)
+                    *reinterpret_cast<f32x4 *>(sh.o + (nt * 16 + n16) * kOStride + mt * 64 + g * 16) = acc[nt][mt] * inv;
+            }
+        }
+        __syncthreads();
+        for (int piece = tid; piece < rows * 32; piece += kThreads) {   // 32 pieces per row
+            const int r = piece >> 5, c = piece & 31;
+            const size_t rh = (size_t)(row0 + r / group) * p.Hq + kvh * group + r % group;
+            __builtin_nontemporal_store(*reinterpret_cast<const f32x4 *>(sh.o + r * kOStride + c * 16),
+                                        reinterpret_cast<f32x4 *>(p.out + rh * kD + c * 4));
         }
         return;
     }
