@@ -89,7 +89,9 @@ def main():
     rej_bytes = w.reject_algorithmic_bytes() if mode == sv.ACCEPT_SAMPLE else w.T * w.V * 4
     step_bytes = attn_bytes + rej_bytes
     kv_bytes = 2 * ds.k_cache.numel() * ds.k_cache.element_size()
-    nrot = args.rotate or max(2, int(np.ceil(1.2e9 / max(kv_bytes + rej_bytes, 1))))
+    # at least four copies and 4 GB in all: with two copies of a 1 GB workload the 256 MB
+    # last-level cache still served a few per cent of the (non-temporal) reads
+    nrot = args.rotate or max(4, int(np.ceil(4.0e9 / max(kv_bytes + rej_bytes, 1))))
     nrot = min(nrot, 16)
 
     # rotated copies: same bytes at different addresses
