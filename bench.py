@@ -95,20 +95,7 @@ def main():
     nrot = min(nrot, 16)
 
     # rotated copies: same bytes at different addresses
-    variants = []
-    for i in range(nrot):
-        if i == 0:
-            variants.append((ds.attn_args, ds.reject_args, None))
-            continue
-        kc, vc = ds.k_cache.clone(), ds.v_cache.clone()
-        tl = ds.target_logits.clone()
-        dl = ds.draft_logits.clone() if ds.draft_logits is not None else None
-        a, ka = sv.make_attn_args(ds.q, kc, vc, ds.block_table, ds.kv_len, ds.cu_q_len, ds.out, w.kv_len,
-                                  w.cu_q_len, Hkv=w.Hkv, kv_layout=sv.KV_MFMA)
-        r, kr = sv.make_reject_args(tl, dl, ds.draft_tokens, ds.cu_q_len, w.cu_q_len, ds.accepted_len,
-                                    ds.next_token, ds.counters, philox_seed=w.philox_seed,
-                                    philox_step=w.philox_step, out_tokens=ds.out_tokens, accept_mode=mode)
-        variants.append((a, r, (ka, kr)))
+    variants = [(a, r, None) for a, r in ds.rotated(nrot)]
 
     stream = torch.cuda.current_stream()
 

@@ -24,6 +24,7 @@ class DeviceStep:
         self.w = w
         self.device = device
         self.kv_layout = kv_layout
+        self.accept_mode = accept_mode
         self.q = _to_device_kv(w.q, device)
         k_tm = _to_device_kv(w.k_pages, device)
         v_tm = _to_device_kv(w.v_pages, device)
@@ -58,6 +59,35 @@ class DeviceStep:
             philox_step=w.philox_step, out_tokens=self.out_tokens, debug_u_ratio=self.debug,
             accept_mode=accept_mode)
         self.workspace = sv.alloc_workspace(sv.spec_verify_workspace_bytes(self.attn_args, self.reject_args), device)
+
+    def rotated(self, copies: int):
+        """``copies`` argument pairs for the same step whose KV pools and logits live at different
+        addresses (the first pair is this object's own), for timing loops that must not find their
+        inputs in the 256 MB last-level cache.  The copies stay alive with this object."""
+        pairs = [(self.attn_args, self.reject_args)]
+        self._rotated_keep = []
+        w = self.w
+        for _ in range(max(copies, 1) - 1):
+            kc, vc = self.k_cache.clone(), self.v_cache.clone()
+            tl = self.target_logits.clone()
+            dl = self.draft_logits.clone() if self.draft_logits is not None else None
+            a, keep_a = sv.make_attn_args(self.q, kc, vc, self.block_table, self.kv_len, self.cu_q_len, self.out,
+                                          w.kv_len, w.cu_q_len, Hkv=w.Hkv, kv_layout=self.kv_layout)
+            r, keep_r = sv.make_reject_args(tl, dl, self.draft_tokens, self.cu_q_len, w.cu_q_len, self.accepted_len,
+                                            self.next_token, self.counters, philox_seed=w.philox_seed,
+                                            philox_step=w.philox_step, out_tokens=self.out_tokens,
+                                            debug_u_ratio=self.debug, accept_mode=self.accept_mode)
+            pairs.append((a, r))
+            self._rotated_keep.append((kc, vc, tl, dl, keep_a, keep_r))
+        return pairs
+
+    def input_bytes(self) -> int:
+        """Bytes of the big inputs (K and V pools, logits) of one copy."""
+        n = 2 * self.k_cache.numel() * self.k_cache.element_size()
+        n += self.target_logits.numel() * 4
+        if self.draft_logits is not None:
+            n += self.draft_logits.numel() * 4
+        return n
 
     def run_attn(self, stream=None):
         sv.spec_verify_attn(self.attn_args, self.workspace, stream)
