@@ -203,7 +203,12 @@ RejectPlan plan_reject(const spec_reject_args *r, size_t base)
     pl.stat_seg_len = seg_len;
     pl.stat_segments = (r->V + seg_len - 1) / seg_len;
     // race: about 512 blocks in all, segments of >= 2048 vocabulary ids, at most 64 per request
-    int rsegs = (512 + r->B - 1) / r->B;
+    int race_blocks = 512;
+    if (const char *e = getenv("SPEC_VERIFY_RACE_BLOCKS")) {   // tuning switch
+        const int v = atoi(e);
+        if (v >= 1 && v <= 65536) race_blocks = v;
+    }
+    int rsegs = (race_blocks + r->B - 1) / r->B;
     const int rmax_by_len = (r->V + 2047) / 2048;
     if (rsegs > rmax_by_len) rsegs = rmax_by_len;
     if (rsegs > 64) rsegs = 64;
