@@ -53,6 +53,8 @@ struct AttnParams {
     float reject_span;            // fraction of the attention items among which the rejection items are spread in the grid
     int32_t split_p;              // feed the softmax weights to the PV product as bf16 high + low parts
     int32_t single_chunk_direct;  // requests with one chunk were written straight to `out`: the combine kernel skips them
+    int32_t reject_even_xcds;     // fused step: rejection blocks only at even positions of the grid's rows of 8 (see GridSplit)
+    int32_t reject_even_limit;    // ... when there are at most this many attention blocks (the number of compute units)
     int32_t reserved;
     const void *q, *k_cache, *v_cache;
     const int32_t *block_table, *kv_len, *cu_q_len;
@@ -61,7 +63,7 @@ struct AttnParams {
     float *ws_ml;
     unsigned long long *tickets;
 };
-static_assert(sizeof(AttnParams) == 18 * 4 + 10 * 8, "AttnParams has padding");
+static_assert(sizeof(AttnParams) == 20 * 4 + 10 * 8, "AttnParams has padding");
 
 // ---------------------------------------------------------------- rejection
 // Records handed between the rejection stages are arrays of 8-byte words, each a

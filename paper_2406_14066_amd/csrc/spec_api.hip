@@ -272,6 +272,9 @@ AttnParams attn_params(const spec_attn_args *a, const AttnPlan &pl, char *ws)
         if (v >= 0 && v <= (1 << 20)) p.attn_first_limit = (int32_t)v;
     }
     if (const char *e = getenv("SPEC_VERIFY_SPLIT_P")) p.split_p = (e[0] != '0');   // experiment switch
+    p.reject_even_xcds = 1;
+    p.reject_even_limit = compute_units();
+    if (const char *e = getenv("SPEC_VERIFY_REJECT_EVEN")) p.reject_even_xcds = (e[0] != '0');   // tuning switch
     return p;
 }
 

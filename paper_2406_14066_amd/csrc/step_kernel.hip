@@ -1219,6 +1219,7 @@ struct GridSplit {
     int n_stat, n_reject, n_attn;
     int attn_first;
     int rows_attn_mixed;   // attention rows among which the rejection rows are spread; the other attention rows follow
+    int reject_cols;       // positions of a row of 8 blocks that carry rejection items: all 8, or the 4 even ones
 };
 
 // All kernel arguments in one struct, so that the place of the order table inside the
@@ -1240,19 +1241,36 @@ __global__ __launch_bounds__(kThreads, 2) void spec_step_kernel(StepArgs args)
     bool is_attn = HAS_ATTN;
     if constexpr (HAS_ATTN && HAS_REJECT) {
         if (gs.attn_first) {
-            is_attn = item < gs.n_attn;
-            if (!is_attn) item -= gs.n_attn;
+            const int n_attn_rows8 = (gs.n_attn + kXcds - 1) / kXcds * kXcds;   // whole rows: positions keep their XCD
+            is_attn = item < n_attn_rows8;
+            if (is_attn) {
+                if (item >= gs.n_attn) return;   // padding of the last attention row
+            } else {
+                item -= n_attn_rows8;
+                if (gs.reject_cols != kXcds) {
+                    if (item & 1) return;
+                    item >>= 1;
+                }
+                if (item >= gs.n_reject) return;
+            }
         } else {
             // rows of kXcds consecutive blocks (one per XCD, the hardware deals blocks to the
             // XCDs round-robin) share a role, so every XCD sees the same mix
             const int row = item / kXcds, col = item % kXcds;
             const long long rows_attn = gs.rows_attn_mixed;
-            const long long rows_all = rows_attn + (gs.n_reject + kXcds - 1) / kXcds;
+            const long long rows_all = rows_attn + (gs.n_reject + gs.reject_cols - 1) / gs.reject_cols;
             if (row < rows_all) {
                 const int before = (int)((row * rows_attn) / rows_all);
                 const int upto = (int)(((row + 1) * rows_attn) / rows_all);
                 is_attn = upto > before;
-                item = (is_attn ? before : row - before) * kXcds + col;
+                if (is_attn) {
+                    item = before * kXcds + col;
+                } else if (gs.reject_cols == kXcds) {
+                    item = (row - before) * kXcds + col;
+                } else {
+                    if (col & 1) return;
+                    item = (row - before) * (kXcds / 2) + (col >> 1);
+                }
             } else {   // the attention rows after the last rejection row
                 is_attn = true;
                 item = (int)(rows_attn + (row - rows_all)) * kXcds + col;
@@ -1310,7 +1328,17 @@ hipError_t launch(const AttnParams &ap, const RejectParams &rp, int n_stat, int 
     gs.rows_attn_mixed = (int)(rows_attn_all * (double)ap.reject_span);
     if (gs.rows_attn_mixed < 1) gs.rows_attn_mixed = 1;
     if (gs.rows_attn_mixed > rows_attn_all) gs.rows_attn_mixed = rows_attn_all;
-    const dim3 grid(mixed ? ((n_attn + kXcds - 1) / kXcds + (n_reject + kXcds - 1) / kXcds) * kXcds : n_reject + n_attn);
+    // XCDs 1, 3, 5, 7 of this device stream from memory some 6% slower than XCDs 0, 2, 4, 6 (block
+    // traces of equal attention blocks), and a launch ends with its slowest XCD.  When there is at
+    // most one attention block per compute unit (all resident from the start, the rejection blocks
+    // beside them), the rejection blocks, which slow down the attention block they share a compute
+    // unit with, go to the even XCDs only: even positions of a row of 8 blocks; the odd positions
+    // of such rows exit at once.  (With more attention blocks it does not pay: measured 1% slower
+    // with two per compute unit, 15% slower where the rejection half is a fifth of the step.)
+    gs.reject_cols = (HAS_ATTN && HAS_REJECT && ap.reject_even_xcds && n_attn <= ap.reject_even_limit) ? kXcds / 2 : kXcds;
+    const int rows_reject = (n_reject + gs.reject_cols - 1) / gs.reject_cols;
+    const dim3 grid(mixed ? (rows_attn_all + rows_reject) * kXcds
+                          : (HAS_ATTN && HAS_REJECT ? (rows_attn_all + rows_reject) * kXcds : n_reject + n_attn));
     // (with events the extended launch attaches them to the kernel's own begin and end)
     if (HAS_ATTN && !ap.split_p) {
         if (ev.start != nullptr)
