@@ -81,6 +81,7 @@ struct RejectPlan {
     size_t stats_off, stats_bytes;         // [rows][stat_segments][3] words
     size_t partial_off, partial_bytes;     // race partials [B][race_segments][2], then race info [B]
     size_t total_bytes;
+    int32_t early_stop, uniform_k;         // see RejectParams
 };
 
 struct RejectParams {
@@ -92,6 +93,8 @@ struct RejectParams {
     int32_t race_segments, race_seg_len;
     int32_t spin_limit;                  // polls a consumer block spends waiting for its producers
     uint32_t generation;
+    int32_t early_stop;                  // statistics in position order, rows after a request's first rejection are not read (see stats_role)
+    int32_t uniform_k;                   // with early_stop: every request's draft length
     const float *target_logits, *draft_logits;
     const int32_t *draft_tokens, *cu_q_len;
     int32_t *accepted_len, *next_token, *out_tokens;
@@ -103,7 +106,7 @@ struct RejectParams {
     unsigned long long *race_partial;    // [B][race_segments][2]
     unsigned long long *race_info;       // [B]
 };
-static_assert(sizeof(RejectParams) == 14 * 4 + 15 * 8, "RejectParams has padding");
+static_assert(sizeof(RejectParams) == 16 * 4 + 15 * 8, "RejectParams has padding");
 
 // Order in which the attention items take the requests (longest first), passed as a
 // kernel argument.  n == 0: the given order.

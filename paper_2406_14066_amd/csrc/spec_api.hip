@@ -218,6 +218,20 @@ RejectPlan plan_reject(const spec_reject_args *r, size_t base)
     pl.race_seg_len = rlen;
     pl.race_segments = (r->V + rlen - 1) / rlen;
 
+    // Early stop: with many rows (several rounds of statistics blocks anyway) and one draft length
+    // for all requests, the statistics items are taken in position order and the rows after a
+    // request's first rejection are not read at all.
+    pl.early_stop = 0;
+    pl.uniform_k = 0;
+    if (r->T > r->B && r->T % r->B == 0) {
+        const int q = r->T / r->B;
+        bool uniform = true;
+        for (int b = 0; b < r->B && uniform; ++b) uniform = r->host_cu_q_len[b + 1] - r->host_cu_q_len[b] == q;
+        const bool many = (int64_t)rows * pl.stat_segments >= 3ll * compute_units();   // (measured: pays at 768 items, not at 288)
+        bool wanted = many;
+        if (const char *e = getenv("SPEC_VERIFY_EARLY_STOP")) wanted = e[0] != '0';   // tuning switch
+        if (uniform && wanted) { pl.early_stop = 1; pl.uniform_k = q - 1; }
+    }
     pl.stats_off = base;
     pl.stats_bytes = align_up((size_t)rows * pl.stat_segments * kStatWords * sizeof(unsigned long long));
     pl.partial_off = pl.stats_off + pl.stats_bytes;
@@ -296,6 +310,7 @@ RejectParams reject_params(const spec_reject_args *r, const RejectPlan &pl, char
     p.kv_len = r->kv_len; p.new_kv_len = r->new_kv_len; p.draft_next_len = r->draft_next_len;
     p.stat_segments = pl.stat_segments; p.stat_seg_len = pl.stat_seg_len;
     p.race_segments = pl.race_segments; p.race_seg_len = pl.race_seg_len;
+    p.early_stop = pl.early_stop; p.uniform_k = pl.uniform_k;
     p.spin_limit = 1 << 20;   // about a second of polling; never reached in a healthy launch
     p.stats = reinterpret_cast<unsigned long long *>(ws + pl.stats_off);
     p.race_partial = reinterpret_cast<unsigned long long *>(ws + pl.partial_off);

@@ -19,6 +19,9 @@
 // lowest id) per (target row, segment) in the statistics stage and has no race; a
 // point-mass draft needs statistics of the target rows only and leaves the rejected
 // token out of the race.
+// Large batches with one draft length take the statistics items in position order and skip
+// the rows after a request's first rejection (stats_role): the accept chain of a request
+// stops there (Section 4), so those rows decide nothing.
 // The rejection items keep that order among themselves and are mixed into the first part
 // of the attention items (see GridSplit), so that the rejection half, whose stages depend
 // on each other, runs underneath the attention stream and is done before it.
@@ -456,7 +459,7 @@ __device__ __forceinline__ bool wait_all(int spin_limit, F probe)
 // recomputes it.  Waits (bounded) until all of the request's statistics carry this
 // call's tag.  Leaves log2-sum-exp per row in sh.lse2, m in sh.m, the near-tie count
 // in sh.near.  Returns false if the statistics never arrived.
-__device__ __forceinline__ bool accept_phase(const RejectParams &p, int b, RejectShared &sh, bool write_debug)
+__device__ __forceinline__ bool accept_phase(const RejectParams &p, int b, RejectShared &sh, bool write_debug, int npos = -1)
 {
     const int tid = threadIdx.x;
     const int row_t0 = uniform_load(p.cu_q_len, b);
@@ -465,10 +468,13 @@ __device__ __forceinline__ bool accept_phase(const RejectParams &p, int b, Rejec
     const bool has_draft_rows = p.mode == SPEC_ACCEPT_SAMPLE;
     const int nrows = has_draft_rows ? 2 * k + 1 : k + 1;
     const int nstat = nrows * p.stat_segments;
+    // npos >= 0: only the first npos positions (their target and draft rows) are looked at, and
+    // sh.m counts the leading accepts among them
+    const int npos_eval = npos < 0 ? k : npos;
 
     // the draft tokens' logits do not depend on the statistics: fetch them first
     float tx = 0.0f, dx = 0.0f;
-    if (tid < k) {
+    if (tid < npos_eval) {
         const int x = p.draft_tokens[row_d0 + tid];
         tx = p.target_logits[(size_t)(row_t0 + tid) * p.V + x];
         if (has_draft_rows) dx = p.draft_logits[(size_t)(row_d0 + tid) * p.V + x];
@@ -480,6 +486,7 @@ __device__ __forceinline__ bool accept_phase(const RejectParams &p, int b, Rejec
         for (int i = tid; i < nstat; i += kThreads) {
             const int ri = i / p.stat_segments;
             const int sg = i - ri * p.stat_segments;
+            if (npos >= 0 && (ri <= k ? ri : ri - k - 1) >= npos) continue;   // a row of a later position
             const int row = ri <= k ? row_t0 + ri : p.T + row_d0 + (ri - k - 1);
             const unsigned long long *st = p.stats + 3 * ((size_t)row * p.stat_segments + sg);
             const unsigned long long w0 = fetch_u64(st), w1 = fetch_u64(st + 1), w2 = fetch_u64(st + 2);
@@ -490,7 +497,7 @@ __device__ __forceinline__ bool accept_phase(const RejectParams &p, int b, Rejec
         return mine;
     });
     if (!ok) return false;
-    if (tid < nrows) {
+    if (tid < nrows && (npos < 0 || (tid <= k ? tid : tid - k - 1) < npos)) {
         float mx = kEmptyMax;
         for (int sg = 0; sg < p.stat_segments; ++sg) mx = fmaxf(mx, sh.seg_off[tid][sg]);
         double total = 0.0;
@@ -501,7 +508,7 @@ __device__ __forceinline__ bool accept_phase(const RejectParams &p, int b, Rejec
     __syncthreads();
 
     // accept tests, all evaluated in parallel; the chain is resolved below
-    if (tid < k) {
+    if (tid < npos_eval) {
         const double log2_p = (double)tx * kLog2eD - sh.lse2[tid];
         const double log2_q = has_draft_rows ? (double)dx * kLog2eD - sh.lse2[k + 1 + tid] : 0.0;   // point mass: q(x) = 1
         const double ratio = exp2(log2_p - log2_q);  // p = 0 -> 0, q = 0 < p -> inf, both 0 -> NaN (rejects)
@@ -515,9 +522,9 @@ __device__ __forceinline__ bool accept_phase(const RejectParams &p, int b, Rejec
     __syncthreads();
     if (tid == 0) {
         int m = 0;
-        while (m < k && sh.accept[m]) ++m;
+        while (m < npos_eval && sh.accept[m]) ++m;
         int near = 0;
-        const int evaluated = m + 1 < k ? m + 1 : k;
+        const int evaluated = m + 1 < npos_eval ? m + 1 : npos_eval;
         for (int i = 0; i < evaluated; ++i)
             if (fabs(sh.u[i] - sh.ratio[i]) < 1e-6) ++near;
         sh.m = m;
@@ -532,6 +539,49 @@ __device__ __forceinline__ bool accept_phase(const RejectParams &p, int b, Rejec
     return true;
 }
 
+// Greedy mode: how many of the first npos draft tokens of request b equal their row's arg-max
+// (a leading run), from the arg-max records of the target rows 0 .. npos-1.  Waits (bounded)
+// for those records; the result is left in sh.m.  Returns false if they never arrived.
+__device__ __forceinline__ bool greedy_prefix(const RejectParams &p, int b, int npos, RejectShared &sh)
+{
+    const int tid = threadIdx.x;
+    const int row_t0 = uniform_load(p.cu_q_len, b);
+    const int row_d0 = row_t0 - b;
+    const int nstat = npos * p.stat_segments;
+    const bool ok = wait_all(p.spin_limit, [&] {
+        bool mine = true;
+        for (int i = tid; i < nstat; i += kThreads) {
+            const int ri = i / p.stat_segments;
+            const int sg = i - ri * p.stat_segments;
+            const unsigned long long *st = p.stats + 3 * ((size_t)(row_t0 + ri) * p.stat_segments + sg);
+            const unsigned long long w0 = fetch_u64(st), w1 = fetch_u64(st + 1);
+            mine = mine && tagged_ok(w0, p.generation) && tagged_ok(w1, p.generation);
+            sh.seg_off[ri][sg] = __uint_as_float((uint32_t)w0);
+            sh.seg_sum[ri][sg] = (double)(uint32_t)w1;   // the id, exactly
+        }
+        return mine;
+    });
+    if (!ok) return false;
+    if (tid < npos) {
+        float best = -INFINITY;
+        int best_id = 0x7FFFFFFF;
+        for (int sg = 0; sg < p.stat_segments; ++sg) {
+            const float v = sh.seg_off[tid][sg];
+            const int id = (int)sh.seg_sum[tid][sg];
+            if (v > best || (v == best && id < best_id)) { best = v; best_id = id; }
+        }
+        sh.accept[tid] = p.draft_tokens[row_d0 + tid] == (best_id == 0x7FFFFFFF ? 0 : best_id) ? 1 : 0;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int m = 0;
+        while (m < npos && sh.accept[m]) ++m;
+        sh.m = m;
+    }
+    __syncthreads();
+    return true;
+}
+
 // Statistics items are ordered by request (its target rows, then its draft rows), so that
 // the first requests' statistics are complete early and their races can start while
 // later requests' rows are still being read.
@@ -540,6 +590,51 @@ __device__ __forceinline__ void stats_role(const RejectParams &p, int item, Reje
 {
     const int rec = item / p.stat_segments;          // (request, row of the request)
     const int seg = item - rec * p.stat_segments;
+    if (p.early_stop) {
+        // Position order (every request has uniform_k draft tokens): the target and draft rows (the
+        // target rows, if the draft is a point mass) of position 0 of all requests, then those of
+        // position 1, ..., then the bonus rows.  The rows
+        // of a position are only needed if the request's earlier positions were all accepted; by
+        // the time a block of position j starts, the statistics of positions < j were dispatched
+        // long before (two items per request and position), so the check costs a round trip, not a
+        // wait.  A row that is not needed gets a placeholder record, so that later stages, which
+        // poll all of a request's records and use those up to the first rejection, find it.
+        const int k = p.uniform_k;
+        const bool has_draft_rows = p.mode == SPEC_ACCEPT_SAMPLE;
+        const int per_position = has_draft_rows ? 2 * p.B : p.B;
+        int j, b;
+        bool is_draft = false;
+        if (rec < per_position * k) {
+            j = rec / per_position;
+            const int w = rec - j * per_position;
+            b = has_draft_rows ? w >> 1 : w;
+            is_draft = has_draft_rows && (w & 1) != 0;
+        } else {
+            j = k;
+            b = rec - per_position * k;
+        }
+        const int row_t0 = b * (k + 1);
+        const int row = is_draft ? p.T + (row_t0 - b) + j : row_t0 + j;
+        const bool greedy = p.mode == SPEC_ACCEPT_GREEDY;
+        if (j > 0 && (greedy ? greedy_prefix(p, b, j, sh) : accept_phase(p, b, sh, false, j)) && sh.m < j) {
+            if (threadIdx.x == 0) {
+                unsigned long long *dst = p.stats + 3 * ((size_t)row * p.stat_segments + seg);
+                if (greedy) {   // (largest logit, id) of nothing
+                    publish_tagged(dst + 0, __float_as_uint(-INFINITY), p.generation);
+                    publish_tagged(dst + 1, 0x7FFFFFFFu, p.generation);
+                } else {        // sum 1, offset 0
+                    const unsigned long long bits = (unsigned long long)__double_as_longlong(1.0);
+                    publish_tagged(dst + 0, (uint32_t)bits, p.generation);
+                    publish_tagged(dst + 1, (uint32_t)(bits >> 32), p.generation);
+                    publish_tagged(dst + 2, __float_as_uint(0.0f), p.generation);
+                }
+            }
+            return;
+        }
+        if (greedy) argmax_block(p, row, seg, sh);
+        else stats_block<UNROLL>(p, row, seg, sh);
+        return;
+    }
     if (p.mode != SPEC_ACCEPT_SAMPLE) {   // target rows only: rec is the row
         if (p.mode == SPEC_ACCEPT_GREEDY) argmax_block(p, rec, seg, sh);
         else stats_block<UNROLL>(p, rec, seg, sh);

@@ -74,6 +74,26 @@ def test_greedy_small(harness, name, B, V, k):
     assert len(seen) > 1   # the cases exercise more than one accepted length
 
 
+@pytest.mark.parametrize("B,V,k", [(16, 1024, 1), (7, 4100, 4), (5, 32000, 8), (3, 128256, 3)], ids=["k1", "k4", "k8", "v128256"])
+def test_greedy_with_early_stop(harness, monkeypatch, B, V, k):
+    """Greedy acceptance with the arg-max pass in position order (rows after a request's first
+    mismatch are skipped); the library picks that order for large batches only, the switch forces it."""
+    print("case greedy early stop", B, V, k, flush=True)
+    monkeypatch.setenv("SPEC_VERIFY_EARLY_STOP", "1")
+    seen = set()
+    for step in range(3):
+        w = _logits_only("ges_k%d" % k, B, V, [k] * B, 90 + step, step)
+        w.draft_tokens = _mostly_argmax_tokens(w, 17 + step)
+        ds = harness.DeviceStep(w, kv_layout=sv.KV_TOKEN_MAJOR, accept_mode=sv.ACCEPT_GREEDY)
+        ds.run_reject()
+        ref = _check_greedy(w, ds.results())
+        seen.update(ref.accepted_len.tolist())
+        ds.counters.zero_()
+        ds.run_reject()   # again on the same workspace
+        _check_greedy(w, ds.results())
+    assert len(seen) > 1
+
+
 def test_greedy_equal_maxima_take_the_lowest_id(harness):
     print("case greedy ties", flush=True)
     w = _logits_only("ties", 4, 4096, [2, 2, 2, 2], 5, 0)
@@ -101,6 +121,21 @@ def test_point_draft_small(harness, name, B, V, k):
         ref = oracle.reject_onehot(w.target_logits, w.draft_tokens, w.cu_q_len, w.philox_seed, w.philox_step)
         near += check_reject(w, ds.results(), ref=ref)["near_ties"]
     print("%s: near ties %d" % (name, near))
+
+
+@pytest.mark.parametrize("B,V,k", [(16, 1024, 1), (7, 4100, 4), (5, 32000, 8)], ids=["k1", "k4", "k8"])
+def test_point_draft_with_early_stop(harness, monkeypatch, B, V, k):
+    """Point-mass draft with the statistics pass in position order (rows after a request's first
+    rejection are skipped); the library picks that order for large batches only, the switch forces it."""
+    print("case point draft early stop", B, V, k, flush=True)
+    monkeypatch.setenv("SPEC_VERIFY_EARLY_STOP", "1")
+    for step in range(2):
+        w = _logits_only("es_k%d" % k, B, V, [k] * B, 80 + step, step)
+        w.draft_tokens = _mostly_argmax_tokens(w, 13 + step, hit=0.8)
+        ds = harness.DeviceStep(w, kv_layout=sv.KV_TOKEN_MAJOR, accept_mode=sv.ACCEPT_POINT_DRAFT)
+        ds.run_reject()
+        ref = oracle.reject_onehot(w.target_logits, w.draft_tokens, w.cu_q_len, w.philox_seed, w.philox_step)
+        check_reject(w, ds.results(), ref=ref)
 
 
 @pytest.mark.parametrize("mode", [sv.ACCEPT_GREEDY, sv.ACCEPT_POINT_DRAFT], ids=["greedy", "point_draft"])

@@ -99,6 +99,47 @@ def test_reject_sample_small(harness, name, kw):
     print("%s: near ties %d" % (name, total_near))
 
 
+EARLY_STOP_CASES = [
+    ("k1_v1024", dict(B=16, V=1024, k=1, sigma=1.0)),
+    ("k4_v4100", dict(B=9, V=4100, k=4, sigma=0.8)),
+    ("k8_v32000", dict(B=6, V=32000, k=8, sigma=0.6)),
+    ("k3_identical", dict(B=5, V=2048, k=3, sigma=0.0)),
+    ("k3_far_apart", dict(B=7, V=2048, k=3, sigma=4.0)),
+]
+
+
+@pytest.mark.parametrize("name,kw", EARLY_STOP_CASES, ids=[c[0] for c in EARLY_STOP_CASES])
+def test_reject_sample_with_early_stop(harness, monkeypatch, name, kw):
+    """The statistics pass in position order, skipping the rows after a request's first rejection
+    (the library chooses it for large batches only; the switch forces it here)."""
+    print("case early stop", name, flush=True)
+    monkeypatch.setenv("SPEC_VERIFY_EARLY_STOP", "1")
+    B = kw["B"]
+    for step in range(3):
+        w = W.make_workload(name, B=B, Hq=1, Hkv=1, d=64, V=kw["V"], dtype="f32", kv_len=[16] * B, k=[kw["k"]] * B,
+                            draft_std=3.0, sigma=kw["sigma"], data_seed=29 + step, philox_seed=0x1234567,
+                            philox_step=(9 << 32) + step, with_kv=False)
+        w.k_pages = w.v_pages = np.zeros((1, 1, 16, 64), np.float32)
+        w.q = np.zeros((w.T, 1, 64), np.float32)
+        ds, res = _run(harness, w, sv.KV_TOKEN_MAJOR, "reject")
+        check_reject(w, res)
+        if name == "k3_identical":
+            np.testing.assert_array_equal(res["accepted_len"], w.k)
+        # a second call on the same workspace (the placeholder records were cleared)
+        ds.counters.zero_()
+        ds.run_reject()
+        check_reject(w, ds.results())
+
+
+def test_whole_step_with_early_stop(harness, monkeypatch):
+    print("case early stop, fused step", flush=True)
+    monkeypatch.setenv("SPEC_VERIFY_EARLY_STOP", "1")
+    w = W.config("c4", B=24, L_scale=0.5)
+    ds, res = _run(harness, w, sv.KV_MFMA)
+    check_attn(w, res["out"])
+    check_reject(w, res)
+
+
 def test_counters_accumulate_and_runs_are_deterministic(harness):
     print("case determinism", flush=True)
     w = W.config("c2", B=2, L_scale=0.25)
