@@ -153,6 +153,12 @@ def main():
                       "achieved_GBps": step_bytes / graph_sec / 1e9}
     res = ds.results()
     emitted_per_step = int(res["counters"][3]) // max(int(res["counters"][5]) // w.B, 1)
+    # logit bytes of the rows up to each request's first rejection (what the step needs at least;
+    # large uniform batches are run that way)
+    m = res["accepted_len"].astype(np.int64)
+    kk = w.k.astype(np.int64)
+    rows_needed = (2 if mode == sv.ACCEPT_SAMPLE else 1) * np.minimum(m + 1, kk) + (m == kk)
+    rej_bytes_needed = int(rows_needed.sum()) * w.V * 4
 
     kernel_us = {k: (1e3 * ms / n if n else None) for k, (ms, n) in kt.items()}
     step_us = kernel_us["step"]
@@ -200,6 +206,7 @@ def main():
             "algorithmic_bytes_per_launch": step_bytes,
             "attention_bytes": attn_bytes,
             "rejection_bytes": rej_bytes,
+            "rejection_bytes_up_to_first_rejection": rej_bytes_needed,
             "events_in_timed_region": events_in_region,
         },
     }
