@@ -136,7 +136,9 @@ typedef enum {
 typedef struct {
     int32_t B, V, T;
     const float *target_logits;   /* [T][V]; request b owns rows cu_q_len[b] .. cu_q_len[b]+k_b */
-    const float *draft_logits;    /* [T-B][V]; request b owns rows cu_q_len[b]-b .. +k_b-1; row i produced x_i */
+    const float *draft_logits;    /* [T-B][V]; request b owns rows cu_q_len[b]-b .. +k_b-1; row i produced x_i.
+                                     The rows of positions after a request's first rejection decide nothing
+                                     (Section 4: the accept chain stops there) and may be left unread. */
     const int32_t *draft_tokens;  /* [T-B] */
     const int32_t *cu_q_len;      /* [B+1] */
     const int32_t *host_cu_q_len; /* HOST copy (validation and launch planning) */
