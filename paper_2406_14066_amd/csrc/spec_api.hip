@@ -186,7 +186,9 @@ AttnPlan plan_attn(const spec_attn_args *a)
     return pl;
 }
 
-RejectPlan plan_reject(const spec_reject_args *r, size_t base)
+// attn_us: rough duration of the attention half that runs in the same launch (microseconds), or
+// negative if the rejection half runs alone.
+RejectPlan plan_reject(const spec_reject_args *r, size_t base, double attn_us = -1.0)
 {
     RejectPlan pl;
     memset(&pl, 0, sizeof pl);
@@ -218,17 +220,26 @@ RejectPlan plan_reject(const spec_reject_args *r, size_t base)
     pl.race_seg_len = rlen;
     pl.race_segments = (r->V + rlen - 1) / rlen;
 
-    // Early stop: with many rows (several rounds of statistics blocks anyway) and one draft length
-    // for all requests, the statistics items are taken in position order and the rows after a
-    // request's first rejection are not read at all.
+    // Early stop: with one draft length for all requests the statistics items can be taken in
+    // position order and the rows after a request's first rejection left unread.  That turns the
+    // pass into a chain of k+1 dependent stages (about 12 us each, then the race), which must stay
+    // hidden: under an attention half that takes clearly longer than the chain, or, when the
+    // rejection half runs alone, behind several rounds of blocks per position.  Measured (step
+    // with / without): B=256 k=2 (64/8 heads) -4%, B=64 k=8 (32/32 heads, L=1024) -8%, B=64 k=4 -3%,
+    // B=32 k=4 +2%, B=32 k=8 +16%, B=8 k=4 +32%.
     pl.early_stop = 0;
     pl.uniform_k = 0;
     if (r->T > r->B && r->T % r->B == 0) {
         const int q = r->T / r->B;
         bool uniform = true;
         for (int b = 0; b < r->B && uniform; ++b) uniform = r->host_cu_q_len[b + 1] - r->host_cu_q_len[b] == q;
-        const bool many = (int64_t)rows * pl.stat_segments >= 3ll * compute_units();   // (measured: pays at 768 items, not at 288)
-        bool wanted = many;
+        bool wanted;
+        if (attn_us >= 0.0) {
+            wanted = 12.0 * q + 30.0 <= 0.75 * attn_us;
+        } else {
+            const int64_t per_position = (int64_t)(r->accept_mode == SPEC_ACCEPT_SAMPLE ? 2 : 1) * r->B * pl.stat_segments;
+            wanted = (int64_t)rows * pl.stat_segments >= 3ll * compute_units() && per_position >= compute_units();
+        }
         if (const char *e = getenv("SPEC_VERIFY_EARLY_STOP")) wanted = e[0] != '0';   // tuning switch
         if (uniform && wanted) { pl.early_stop = 1; pl.uniform_k = q - 1; }
     }
@@ -418,7 +429,11 @@ spec_status spec_verify_step(const spec_attn_args *attn, const spec_reject_args 
     if (st != SPEC_OK) return st;
     if (attn->B != reject->B || attn->T != reject->T) return SPEC_EINVAL;
     const AttnPlan apl = plan_attn(attn);
-    const RejectPlan rpl = plan_reject(reject, apl.total_bytes);
+    // (the KV bytes at 5.5 TB/s: what the attention half takes when it streams well)
+    double kv_bytes = 0.0;
+    for (int b = 0; b < attn->B; ++b) kv_bytes += (double)attn->host_kv_len[b];
+    kv_bytes *= 2.0 * attn->Hkv * attn->d * (attn->qkv_dtype == SPEC_BF16 ? 2 : 4);
+    const RejectPlan rpl = plan_reject(reject, apl.total_bytes, apl.use_mfma ? kv_bytes / 5.5e6 : -1.0);
     st = check_workspace(workspace, workspace_bytes, apl.total_bytes + rpl.total_bytes);
     if (st != SPEC_OK) return st;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
