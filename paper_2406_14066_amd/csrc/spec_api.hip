@@ -226,7 +226,7 @@ RejectPlan plan_reject(const spec_reject_args *r, size_t base, double attn_us = 
     // hidden: under an attention half that takes clearly longer than the chain, or, when the
     // rejection half runs alone, behind several rounds of blocks per position.  Measured (step
     // with / without): B=256 k=2 (64/8 heads) -4%, B=64 k=8 (32/32 heads, L=1024) -8%, B=64 k=4 -3%,
-    // B=32 k=4 +2%, B=32 k=8 +16%, B=8 k=4 +32%.
+    // B=32 k=1..3 -2%, B=32 k=4 +2%, B=32 k=8 +16%, B=16 k=2 (L=2048) +2%, B=8 k=4 +32%.
     pl.early_stop = 0;
     pl.uniform_k = 0;
     if (r->T > r->B && r->T % r->B == 0) {
@@ -235,7 +235,7 @@ RejectPlan plan_reject(const spec_reject_args *r, size_t base, double attn_us = 
         for (int b = 0; b < r->B && uniform; ++b) uniform = r->host_cu_q_len[b + 1] - r->host_cu_q_len[b] == q;
         bool wanted;
         if (attn_us >= 0.0) {
-            wanted = 12.0 * q + 30.0 <= 0.75 * attn_us;
+            wanted = r->B >= 32 && 12.0 * q + 30.0 <= 0.85 * attn_us;
         } else {
             const int64_t per_position = (int64_t)(r->accept_mode == SPEC_ACCEPT_SAMPLE ? 2 : 1) * r->B * pl.stat_segments;
             wanted = (int64_t)rows * pl.stat_segments >= 3ll * compute_units() && per_position >= compute_units();
