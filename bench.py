@@ -165,8 +165,9 @@ def main():
                       "achieved_GBps": step_bytes / graph_sec / 1e9}
     res = ds.results()
     emitted_per_step = int(res["counters"][3]) // max(int(res["counters"][5]) // w.B, 1)
-    # logit bytes of the rows up to each request's first rejection (what the step needs at least;
-    # large uniform batches are run that way)
+    # logit bytes of the rows up to each request's first rejection: what the step needs at least
+    # (the library reads no more than these when it takes the statistics pass in position order,
+    # which it does for large batches with one draft length)
     m = res["accepted_len"].astype(np.int64)
     kk = w.k.astype(np.int64)
     rows_needed = (2 if mode == sv.ACCEPT_SAMPLE else 1) * np.minimum(m + 1, kk) + (m == kk)
