@@ -72,6 +72,7 @@ constexpr int kBufferFlags = 0x00020000;   // raw 32-bit buffer descriptor, word
 // stream pushes out what the blocks do come back to (code, block tables, queries, hand-off
 // words); measured on the four large workloads the hint alone takes 8-10% off the step.
 constexpr int kStreamPolicy = 2;           // "nt" bit of a raw buffer load
+constexpr float kRescaleSlack = 8.0f;      // see the online softmax of the attention role
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
@@ -1057,7 +1058,11 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
             float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
             mx = fmaxf(mx, __shfl_xor(mx, 16));
             mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float m_new = fmaxf(m_run[nt], mx);
+            // The reference of the running sums follows the maximum lazily: it is raised only when
+            // a score exceeds it by more than 8 (base-2 units), so weights reach at most 2^8 and
+            // the accumulators are rescaled on few pages instead of on most early ones (the
+            // result is the same up to rounding: numerator and denominator share the reference).
+            const float m_new = mx > m_run[nt] + kRescaleSlack ? mx : m_run[nt];
             const float alpha = fast_exp2(m_run[nt] - m_new);
             f32x4 pr;
 #pragma unroll
