@@ -1030,9 +1030,9 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
         const bool need_mask = page_tok + SPEC_BLOCK_SIZE > first_masked_token;
         const int tbase = page_tok + 4 * g;
 
-        {
+        if (page_tok + SPEC_BLOCK_SIZE > L) {
             // slots past kv_len in the request's last page may hold anything: clear their V
-            // (done on every page, without a branch, so that no load has to be waited for early)
+            // (the branch is the same for the whole wavefront and holds no loads)
             const int nvalid = min(max(L - tbase, 0), 4);
             const uint32_t lo = nvalid >= 2 ? 0xFFFFFFFFu : (nvalid == 1 ? 0x0000FFFFu : 0u);
             const uint32_t hi = nvalid >= 4 ? 0xFFFFFFFFu : (nvalid == 3 ? 0x0000FFFFu : 0u);
