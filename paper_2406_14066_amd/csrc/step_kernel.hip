@@ -1049,7 +1049,8 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk)
                 s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, cur.k[kk]), qreg[nt][kk], s, 0, 0, 0);
-            s *= p.scale_log2;
+            // (the softmax scale, folded with log2 e, is applied inside the exponent's fused
+            // multiply-add below; the maximum commutes with it, the scale being positive)
             if (need_mask) {
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
@@ -1057,22 +1058,23 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
             }
             float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
             mx = fmaxf(mx, __shfl_xor(mx, 16));
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            mx = fmaxf(mx, __shfl_xor(mx, 32)) * p.scale_log2;
             // The reference of the running sums follows the maximum lazily: it is raised only when
             // a score exceeds it by more than 8 (base-2 units), so weights reach at most 2^8 and
             // the accumulators are rescaled on few pages instead of on most early ones (the
             // result is the same up to rounding: numerator and denominator share the reference).
             const float m_new = mx > m_run[nt] + kRescaleSlack ? mx : m_run[nt];
-            const float alpha = fast_exp2(m_run[nt] - m_new);
             f32x4 pr;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) pr[r] = fast_exp2(s[r] - m_new);
-            l_run[nt] = l_run[nt] * alpha + ((pr[0] + pr[1]) + (pr[2] + pr[3]));
-            m_run[nt] = m_new;
-            if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+            for (int r = 0; r < 4; ++r) pr[r] = fast_exp2(fmaf(s[r], p.scale_log2, -m_new));
+            if (__builtin_amdgcn_ballot_w64(m_new != m_run[nt]) != 0) {   // some row's reference moved: rescale
+                const float alpha = fast_exp2(m_run[nt] - m_new);
+                l_run[nt] *= alpha;
 #pragma unroll
                 for (int mt = 0; mt < 8; ++mt) acc[nt][mt] *= alpha;
+                m_run[nt] = m_new;
             }
+            l_run[nt] += (pr[0] + pr[1]) + (pr[2] + pr[3]);
             const bf16x4 p_hi = __builtin_convertvector(pr, bf16x4);
             bf16x4 p_lo;
             if (SPLIT_P) p_lo = __builtin_convertvector(pr - __builtin_convertvector(p_hi, f32x4), bf16x4);
