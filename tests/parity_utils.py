@@ -34,19 +34,28 @@ def oracle_reject(w):
                                 w.philox_seed, w.philox_step)
 
 
-def check_reject(w, res, ref=None):
+def check_reject(w, res, ref=None, max_excluded=0):
     """Bit-exact accepted lengths and tokens for every request whose decisions are not
-    near-ties; near-tie requests are counted and must still hold a valid outcome."""
+    near-ties.  A request is excluded from the bit-exact comparison if one of its evaluated
+    accept tests has |u - p/q| < 1e-6 (the benchmark spec's category) or if the oracle's race
+    margin is below 1e-5 (this build's category for the next-token draw); excluded requests must
+    still hold a valid outcome.  At most ``max_excluded`` requests may be excluded (0 unless a
+    test says otherwise), so the comparison cannot become vacuous; the counts are returned."""
     ref = ref or oracle_reject(w)
     B = w.B
-    near = np.zeros(B, dtype=bool)
+    near_accept = np.zeros(B, dtype=bool)
+    near_race = np.zeros(B, dtype=bool)
     for b in range(B):
         d0 = int(w.cu_q_len[b]) - b
         kb = int(w.q_len[b]) - 1
         u, ratio = ref.dec_u[d0: d0 + kb], ref.dec_ratio[d0: d0 + kb]
         ev = ~np.isnan(u)
-        if np.any(np.abs(u[ev] - ratio[ev]) < ACCEPT_NEAR_TIE) or ref.race_margin[b] < RACE_NEAR_TIE:
-            near[b] = True
+        near_accept[b] = bool(np.any(np.abs(u[ev] - ratio[ev]) < ACCEPT_NEAR_TIE))
+        near_race[b] = bool(ref.race_margin[b] < RACE_NEAR_TIE)
+    near = near_accept | near_race
+    assert int(near.sum()) <= max_excluded, (
+        "%d requests excluded from the bit-exact comparison (accept near ties %d, race near ties %d), allowed %d"
+        % (near.sum(), near_accept.sum(), near_race.sum(), max_excluded))
     ok = ~near
     np.testing.assert_array_equal(res["accepted_len"][ok], ref.accepted_len[ok])
     np.testing.assert_array_equal(res["next_token"][ok], ref.next_token[ok])
@@ -73,4 +82,8 @@ def check_reject(w, res, ref=None):
         fin = np.isfinite(rr) & (rr > 0)
         rel = np.abs(gr[rows_ok][ev][fin] - rr[fin]) / rr[fin]
         assert rel.size == 0 or rel.max() < 1e-6, "p/q relative error %.3e" % rel.max()
-    return dict(near_ties=int(near.sum()), min_race_margin=float(ref.race_margin.min()), ref=ref)
+    # the library's own near-tie counter (evaluated accept tests within 1e-6 of their uniform)
+    if not near_accept.any():
+        assert c[4] == ref.counters[4] == 0
+    return dict(near_ties=int(near.sum()), near_accept=int(near_accept.sum()), near_race=int(near_race.sum()),
+                excluded=int(near.sum()), min_race_margin=float(ref.race_margin.min()), ref=ref)

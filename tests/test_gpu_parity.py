@@ -34,6 +34,7 @@ def test_c1_tiny_fp32(harness):
     ds, res = _run(harness, w, sv.KV_TOKEN_MAJOR)
     err = check_attn(w, res["out"])
     info = check_reject(w, res)
+    _assert_nothing_excluded(info)
     print("c1: attn err %.2e near ties %d" % (err, info["near_ties"]))
 
 
@@ -158,16 +159,28 @@ def test_c2_full(harness):
     ds, res = _run(harness, w, sv.KV_MFMA)
     err = check_attn(w, res["out"])
     info = check_reject(w, res)
+    _assert_nothing_excluded(info)
     print("c2: attn err %.2e near ties %d min race margin %.2e" % (err, info["near_ties"], info["min_race_margin"]))
 
 
-@pytest.mark.parametrize("k,alpha", [(0, 0.7), (1, 0.5), (4, 0.7), (8, 0.9)])
+def _assert_nothing_excluded(info):
+    # on the five named workloads no decision is a near tie: every request is compared bit for bit
+    assert info["excluded"] == 0 and info["near_accept"] == 0 and info["near_race"] == 0, info
+
+
+C3_POINTS = [(k, 0.7) for k in range(9)] + [(4, 0.5), (4, 0.9), (8, 0.9), (1, 0.5)]
+
+
+@pytest.mark.parametrize("k,alpha", C3_POINTS, ids=["k%d_a%.1f" % p for p in C3_POINTS])
 def test_c3_sweep_points(harness, k, alpha):
+    """Every speculation length of the sweep at one acceptance level, and the three levels at one
+    length: the whole attention output (all 32 requests) and every decision against the oracle."""
     w = W.config("c3", k=k, alpha=alpha)
     print("case c3 k=%d alpha=%.1f" % (k, alpha), flush=True)
     ds, res = _run(harness, w, sv.KV_MFMA)
-    err = check_attn(w, res["out"], requests=[0, 13, 31])
+    err = check_attn(w, res["out"])
     info = check_reject(w, res)
+    _assert_nothing_excluded(info)
     # accepted-token count against Eq. 4's general form at the measured per-row acceptance probabilities
     if k > 0:
         expect = 0.0
@@ -184,13 +197,14 @@ def test_c3_sweep_points(harness, k, alpha):
 
 
 def test_c4_full(harness):
+    """All 256 ragged requests: the whole attention output and every decision against the oracle."""
     w = W.config("c4")
     print("case c4 full", flush=True)
     ds, res = _run(harness, w, sv.KV_MFMA)
-    picks = [0, 1, 77, 128, 200, 255, int(np.argmax(w.kv_len)), int(np.argmin(w.kv_len))]
-    err = check_attn(w, res["out"], requests=picks)
+    err = check_attn(w, res["out"])
     info = check_reject(w, res)
-    print("c4: attn err %.2e near ties %d" % (err, info["near_ties"]))
+    _assert_nothing_excluded(info)
+    print("c4: attn err %.2e near ties %d min race margin %.2e" % (err, info["near_ties"], info["min_race_margin"]))
 
 
 def test_c5_full(harness):
@@ -199,4 +213,5 @@ def test_c5_full(harness):
     ds, res = _run(harness, w, sv.KV_MFMA)
     err = check_attn(w, res["out"])
     info = check_reject(w, res)
-    print("c5: attn err %.2e near ties %d" % (err, info["near_ties"]))
+    _assert_nothing_excluded(info)
+    print("c5: attn err %.2e near ties %d min race margin %.2e" % (err, info["near_ties"], info["min_race_margin"]))

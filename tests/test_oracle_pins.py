@@ -435,6 +435,103 @@ def test_race_winner_recomputed_in_python():
         assert r.race_margin[b] <= (srt[-1] - srt[-2]) / srt[-1] + 1e-15
 
 
+def _race_e(seed, step, b, V):
+    return np.array([-math.log(oracle.u_race(seed, step, b, v)) for v in range(V)])
+
+
+@pytest.mark.parametrize("delta", [1e-3, 2e-5, 0.25])
+def test_race_margin_equals_a_constructed_relative_gap(delta):
+    """Bonus row (k = 0, weights r = p): logits are built so that the two best race scores are
+    proportional to 1 + delta and 1 - delta and every other score is a tenth of that.  The margin
+    (smallest relative perturbation of the weights that can change the winner) is then delta by
+    construction: (s_a - s_b) / (s_a + s_b) = delta, every other pair being far apart."""
+    V, seed, step = 8, 77, 5
+    for b in range(3):
+        e = _race_e(seed, step, b, V)
+        want = np.full(V, 0.1)
+        a, c = (2 + b) % V, (5 + b) % V
+        want[a], want[c] = 1.0 + delta, 1.0 - delta
+        logits = np.log(want * e).astype(np.float32)[None, :]         # p_v / e_v proportional to want_v
+        tl = np.tile(logits, (b + 1, 1))                              # B = b + 1 requests of one bonus row each
+        cu = np.arange(b + 2, dtype=np.int32)
+        r = oracle.reject_sample(tl, np.zeros((0, V), np.float32), np.zeros(0, np.int32), cu, seed, step)
+        assert r.next_token[b] == a
+        # fp32 logits move each score by a relative 1e-7 at most
+        assert abs(r.race_margin[b] - delta) < 4e-7, (r.race_margin[b], delta)
+
+
+def test_race_margin_is_the_flipping_threshold_of_a_correction_row():
+    """Correction row (weights max(0, p - q)): perturb every p and q by a relative eps in the
+    direction that hurts the winner most (winner: p down, q up; challenger: p up, q down).
+    Just below the reported margin the winner must survive against every id, just above it some
+    id must overtake: that is what "smallest relative perturbation that can change the winner"
+    means, recomputed here by brute force from scipy's softmax."""
+    V, seed, step = 40, 91, 3
+    rng = np.random.default_rng(5)
+    checked = 0
+    for trial in range(30):
+        tl = (rng.standard_normal((2, V)) * 2).astype(np.float32)
+        dl = (rng.standard_normal((1, V)) * 2).astype(np.float32)
+        x = int(np.argmin(tl[0] - dl[0]))            # the token the target likes least relative to the draft
+        tl[0, x] -= 30.0                             # p(x)/q(x) ~ e^-30: rejected whatever u is
+        r = oracle.reject_sample(tl, dl, np.array([x], np.int32), np.array([0, 2], np.int32), seed, step + trial)
+        assert r.accepted_len[0] == 0
+        p = scipy.special.softmax(tl[0].astype(np.float64))
+        q = scipy.special.softmax(dl[0].astype(np.float64))
+        e = _race_e(seed, step + trial, 0, V)
+        best = int(r.next_token[0])
+        mg = float(r.race_margin[0])
+        assert mg > 0
+
+        def winner_survives(eps):
+            s_best = (p[best] * (1 - eps) - q[best] * (1 + eps)) / e[best]
+            others = (p * (1 + eps) - q * (1 - eps)) / e
+            others[best] = -np.inf
+            return bool((others < s_best).all())
+
+        assert winner_survives(mg * (1 - 1e-6))
+        assert not winner_survives(mg * (1 + 1e-6))
+        checked += 1
+    assert checked == 30
+
+
+def _near_tie_case(eps, seed=12, step=(3 << 32) + 9, b=2, i=1, V=8):
+    """B = b + 1 requests with k = i + 1 draft tokens each; every accept test but (b, i) has
+    p/q = 1 + something large (always accepted); test (b, i) has p(x)/q(x) = u + eps where u is
+    the uniform that test will draw.  Draft rows are flat (q = 1/V); the target row of the
+    constructed test has logit t at x and 0 elsewhere: p(x) = e^t / (e^t + V - 1)."""
+    B, k = b + 1, i + 1
+    u = oracle.u_accept(seed, step, b, i)
+    tl = np.zeros((B * (k + 1), V), np.float32)
+    dl = np.zeros((B * k, V), np.float32)
+    tok = np.full(B * k, 3, np.int32)
+    tl[:, 3] = 4.0                                    # p(3) > 1/V: ratio > 1, always accepted
+    ratio = u + eps
+    t = math.log((V - 1) * ratio / (V - ratio))       # V e^t / (e^t + V - 1) = ratio
+    row = b * (k + 1) + i
+    tl[row, :] = 0.0
+    tl[row, 3] = np.float32(t)
+    cu = (np.arange(B + 1) * (k + 1)).astype(np.int32)
+    return tl, dl, tok, cu, seed, step, u, B, k
+
+
+@pytest.mark.parametrize("eps,accepted,near", [(4e-7, True, 1), (-4e-7, False, 1), (5e-6, True, 0), (-5e-6, False, 0)])
+def test_near_tie_counter_on_a_constructed_accept_test(eps, accepted, near):
+    """counters[4] counts the evaluated accept tests with |u - p/q| < 1e-6.  One test is built to
+    sit eps away from its uniform (the uniform comes from the pinned Philox mapping); the counter
+    must be 1 inside the window and 0 outside, and the decision must follow the sign of eps."""
+    tl, dl, tok, cu, seed, step, u, B, k = _near_tie_case(eps)
+    assert 1e-3 < u < 1 - 1e-3      # the constructed ratio is a valid probability ratio below 1
+    r = oracle.reject_sample(tl, dl, tok, cu, seed, step)
+    b, i = B - 1, k - 1
+    assert r.counters[4] == near
+    assert r.accepted_len[b] == (k if accepted else i)
+    assert (r.accepted_len[:b] == k).all()
+    got_ratio = r.dec_ratio[b * k + i]
+    assert abs(got_ratio - (u + eps)) < 5e-8          # fp32 rounding of the one logit
+    assert r.dec_u[b * k + i] == u
+
+
 def test_counters_accumulate():
     w = W.make_workload("t", B=8, Hq=1, Hkv=1, d=8, V=64, dtype="f32", kv_len=[16] * 8,
                         k=[3] * 8, draft_std=2.0, sigma=1.0, data_seed=2, philox_seed=1, with_kv=False)
