@@ -178,7 +178,9 @@ AttnPlan plan_attn(const spec_attn_args *a)
     }
     pl.max_chunks = (max_len + pl.chunk_tokens - 1) / pl.chunk_tokens;
     pl.fused_combine = (pl.use_mfma && pl.max_chunks <= kMaxFusedChunks) ? 1 : 0;
-    const size_t slots = (size_t)a->T * a->Hq * pl.max_chunks;
+    // (a request that is not split writes its output directly: the matrix kernel needs no partial
+    // slots when no request has a second chunk)
+    const size_t slots = (pl.use_mfma && pl.max_chunks == 1) ? 0 : (size_t)a->T * a->Hq * pl.max_chunks;
     pl.acc_bytes = align_up(slots * a->d * sizeof(float));
     pl.ml_bytes = align_up(slots * 2 * sizeof(float));
     pl.ticket_bytes = align_up((size_t)a->B * a->Hkv * sizeof(unsigned long long));
