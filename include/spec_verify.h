@@ -185,6 +185,24 @@ spec_status spec_reject_sample(const spec_reject_args *reject, void *workspace, 
 spec_status spec_verify_step(const spec_attn_args *attn, const spec_reject_args *reject, void *workspace,
                              size_t workspace_bytes, void *hip_stream);
 
+/*
+ * The whole step for callers that cannot allocate or pass a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments,
+ * results and errors as spec_verify_step, but the workspace is a device array inside the
+ * library (SPEC_STATIC_SCRATCH_BYTES per GPU, held by every GPU the library runs on until the
+ * process ends).  The call allocates and frees nothing.
+ *   - A step whose workspace (spec_verify_workspace_bytes) exceeds SPEC_STATIC_SCRATCH_BYTES is
+ *     refused with SPEC_EWORKSPACE before anything is launched; use spec_verify_step then.
+ *   - The first call on a GPU resolves the array's device address (one runtime query, no
+ *     allocation); make that call outside stream capture.
+ *   - All calls on one GPU share that GPU's array, which keeps the previous call's contents
+ *     (nothing in it has to start at zero: every record carries its call's tag).  Calls that
+ *     overlap in time on one GPU (two streams, two threads) race on it; calls on one stream
+ *     do not.
+ */
+#define SPEC_STATIC_SCRATCH_BYTES (16u << 20)
+spec_status spec_verify_step_static(const spec_attn_args *attn, const spec_reject_args *reject, void *hip_stream);
+
 /* Host-only validation, exactly what the calls above run first. */
 spec_status spec_validate_attn(const spec_attn_args *attn);
 spec_status spec_validate_reject(const spec_reject_args *reject);

@@ -361,6 +361,69 @@ spec_status run_attn_generic(const AttnParams &p, int dtype, hipStream_t stream)
     return err == hipSuccess ? SPEC_OK : SPEC_EHIP;
 }
 
+
+// ---------------------------------------------------------------------------
+// Scratch memory for callers that cannot allocate (spec_verify_step_static): one file-scope
+// device array per GPU, held until the process ends.  In host code the array's name is only
+// a stand-in for the symbol; its device address is resolved once per device, with that device
+// current, and kept.  Each GPU has its own copy of the array at its own address.
+// ---------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[SPEC_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices];
+
+void *static_scratch_of_current_device()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    void *ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (ptr == nullptr) {
+        // (two threads may both resolve it: they get the same address)
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return nullptr;
+        g_scratch_ptr[dev].store(ptr, std::memory_order_release);
+    }
+    return ptr;
+}
+
+// The whole step on a given workspace (shared by spec_verify_step and spec_verify_step_static).
+spec_status step_on_workspace(const spec_attn_args *attn, const spec_reject_args *reject, void *workspace,
+                              size_t workspace_bytes, void *hip_stream)
+{
+    spec_status st = validate_attn(attn);
+    if (st != SPEC_OK) return st;
+    st = validate_reject(reject);
+    if (st != SPEC_OK) return st;
+    if (attn->B != reject->B || attn->T != reject->T) return SPEC_EINVAL;
+    const AttnPlan apl = plan_attn(attn);
+    // (the KV bytes at 5.5 TB/s: what the attention half takes when it streams well)
+    double kv_bytes = 0.0;
+    for (int b = 0; b < attn->B; ++b) kv_bytes += (double)attn->host_kv_len[b];
+    kv_bytes *= 2.0 * attn->Hkv * attn->d * (attn->qkv_dtype == SPEC_BF16 ? 2 : 4);
+    const RejectPlan rpl = plan_reject(reject, apl.total_bytes, apl.use_mfma ? kv_bytes / 5.5e6 : -1.0);
+    st = check_workspace(workspace, workspace_bytes, apl.total_bytes + rpl.total_bytes);
+    if (st != SPEC_OK) return st;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const AttnParams ap = attn_params(attn, apl, static_cast<char *>(workspace));
+    const RejectParams rp = reject_params(reject, rpl, static_cast<char *>(workspace));
+    if (apl.use_mfma) {
+        // the whole step in one launch
+        UnitOrder order_table;
+        const UnitOrder *order = make_order(attn, order_table);
+        hipError_t err = timed_launch(SPEC_KERNEL_STEP, [&](LaunchEvents ev) {
+            return launch_step_fused(&ap, apl.row_tiles, &rp, order, ev, stream);
+        });
+        if (err == hipSuccess && !apl.fused_combine && apl.max_chunks > 1)
+            err = timed(SPEC_KERNEL_ATTN_COMBINE, stream, [&] { return launch_attn_combine(ap, stream); });
+        return err == hipSuccess ? SPEC_OK : SPEC_EHIP;
+    }
+    st = run_attn_generic(ap, attn->qkv_dtype, stream);
+    if (st != SPEC_OK) return st;
+    const hipError_t err =
+        timed_launch(SPEC_KERNEL_REJECT, [&](LaunchEvents ev) { return launch_step_fused(nullptr, 0, &rp, nullptr, ev, stream); });
+    return err == hipSuccess ? SPEC_OK : SPEC_EHIP;
+}
+
 }  // namespace
 
 }  // namespace specv
@@ -425,38 +488,23 @@ spec_status spec_reject_sample(const spec_reject_args *reject, void *workspace, 
 spec_status spec_verify_step(const spec_attn_args *attn, const spec_reject_args *reject, void *workspace,
                              size_t workspace_bytes, void *hip_stream)
 {
+    return step_on_workspace(attn, reject, workspace, workspace_bytes, hip_stream);
+}
+
+spec_status spec_verify_step_static(const spec_attn_args *attn, const spec_reject_args *reject, void *hip_stream)
+{
+    // sizes first, on the host: a step that does not fit is refused before anything touches the GPU
     spec_status st = validate_attn(attn);
     if (st != SPEC_OK) return st;
     st = validate_reject(reject);
     if (st != SPEC_OK) return st;
     if (attn->B != reject->B || attn->T != reject->T) return SPEC_EINVAL;
-    const AttnPlan apl = plan_attn(attn);
-    // (the KV bytes at 5.5 TB/s: what the attention half takes when it streams well)
-    double kv_bytes = 0.0;
-    for (int b = 0; b < attn->B; ++b) kv_bytes += (double)attn->host_kv_len[b];
-    kv_bytes *= 2.0 * attn->Hkv * attn->d * (attn->qkv_dtype == SPEC_BF16 ? 2 : 4);
-    const RejectPlan rpl = plan_reject(reject, apl.total_bytes, apl.use_mfma ? kv_bytes / 5.5e6 : -1.0);
-    st = check_workspace(workspace, workspace_bytes, apl.total_bytes + rpl.total_bytes);
-    if (st != SPEC_OK) return st;
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    const AttnParams ap = attn_params(attn, apl, static_cast<char *>(workspace));
-    const RejectParams rp = reject_params(reject, rpl, static_cast<char *>(workspace));
-    if (apl.use_mfma) {
-        // the whole step in one launch
-        UnitOrder order_table;
-        const UnitOrder *order = make_order(attn, order_table);
-        hipError_t err = timed_launch(SPEC_KERNEL_STEP, [&](LaunchEvents ev) {
-            return launch_step_fused(&ap, apl.row_tiles, &rp, order, ev, stream);
-        });
-        if (err == hipSuccess && !apl.fused_combine && apl.max_chunks > 1)
-            err = timed(SPEC_KERNEL_ATTN_COMBINE, stream, [&] { return launch_attn_combine(ap, stream); });
-        return err == hipSuccess ? SPEC_OK : SPEC_EHIP;
-    }
-    st = run_attn_generic(ap, attn->qkv_dtype, stream);
-    if (st != SPEC_OK) return st;
-    const hipError_t err =
-        timed_launch(SPEC_KERNEL_REJECT, [&](LaunchEvents ev) { return launch_step_fused(nullptr, 0, &rp, nullptr, ev, stream); });
-    return err == hipSuccess ? SPEC_OK : SPEC_EHIP;
+    const size_t need = spec_verify_workspace_bytes(attn, reject);
+    if (need == 0) return SPEC_EINVAL;
+    if (need > SPEC_STATIC_SCRATCH_BYTES) return SPEC_EWORKSPACE;
+    void *ws = static_scratch_of_current_device();
+    if (ws == nullptr) return SPEC_EHIP;
+    return step_on_workspace(attn, reject, ws, SPEC_STATIC_SCRATCH_BYTES, hip_stream);
 }
 
 spec_status spec_kv_append(const spec_kv_append_args *a, void *hip_stream)

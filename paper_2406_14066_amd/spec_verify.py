@@ -66,6 +66,7 @@ class KvAppendArgs(C.Structure):
 
 EXPORTS = (
     "spec_verify_workspace_bytes", "spec_verify_attn", "spec_reject_sample", "spec_verify_step",
+    "spec_verify_step_static",
     "spec_validate_attn", "spec_validate_reject", "spec_kv_repack_mfma", "spec_kv_append", "spec_status_string",
     "spec_verify_version", "spec_profile_begin", "spec_profile_end",
     "spec_expected_generated_len", "spec_predict_latency", "spec_fit_latency",
@@ -100,6 +101,8 @@ def lib():
         L.spec_reject_sample.restype = C.c_int
         L.spec_verify_step.argtypes = [C.POINTER(AttnArgs), C.POINTER(RejectArgs), C.c_void_p, C.c_size_t, C.c_void_p]
         L.spec_verify_step.restype = C.c_int
+        L.spec_verify_step_static.argtypes = [C.POINTER(AttnArgs), C.POINTER(RejectArgs), C.c_void_p]
+        L.spec_verify_step_static.restype = C.c_int
         L.spec_validate_attn.argtypes = [C.POINTER(AttnArgs)]
         L.spec_validate_attn.restype = C.c_int
         L.spec_validate_reject.argtypes = [C.POINTER(RejectArgs)]
@@ -232,6 +235,15 @@ def spec_verify_step(attn: AttnArgs, reject: RejectArgs, workspace, stream=None)
     _check(lib().spec_verify_step(C.byref(attn), C.byref(reject), workspace.data_ptr(),
                                   workspace.numel() * workspace.element_size(), _stream_handle(stream)),
            "spec_verify_step")
+
+
+STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def spec_verify_step_static(attn: AttnArgs, reject: RejectArgs, stream=None) -> None:
+    """The step on the library's own per-GPU scratch array (no workspace argument, no allocation)."""
+    _check(lib().spec_verify_step_static(C.byref(attn), C.byref(reject), _stream_handle(stream)),
+           "spec_verify_step_static")
 
 
 def spec_kv_repack_mfma(src_k, src_v, dst_k, dst_v, stream=None) -> None:

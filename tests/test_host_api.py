@@ -225,3 +225,21 @@ def test_bookkeeping_outputs_need_kv_len():
     assert sv.spec_validate_reject(r) == sv.SPEC_EINVAL
     r.kv_len = FAKE
     assert sv.spec_validate_reject(r) == sv.SPEC_OK
+
+
+def test_static_scratch_entry_refuses_what_does_not_fit():
+    """spec_verify_step_static sizes the step on the host first: a step whose workspace exceeds the
+    library's scratch array is refused before anything touches the GPU, and argument errors come
+    back as from spec_verify_step."""
+    L = sv.lib()
+    # token-major pages take the generic kernel: one partial per (row, head, 256-token chunk)
+    q_len = (9,) * 12
+    a = _attn(B=12, Hq=32, Hkv=8, d=128, kv_len=(8000,) * 12, q_len=q_len, max_blocks=500,
+              dtype=sv.SPEC_BF16, layout=sv.KV_TOKEN_MAJOR)
+    r = _reject(B=12, V=32, q_len=q_len)
+    assert sv.spec_verify_workspace_bytes(a, r) > sv.STATIC_SCRATCH_BYTES
+    assert L.spec_verify_step_static(C.byref(a), C.byref(r), None) == sv.SPEC_EWORKSPACE
+    bad = _attn()
+    bad.q = None
+    assert L.spec_verify_step_static(C.byref(bad), C.byref(_reject()), None) == sv.SPEC_EINVAL
+    assert L.spec_verify_step_static(C.byref(_attn()), C.byref(_reject(B=2, q_len=(2, 2))), None) == sv.SPEC_EINVAL
