@@ -26,6 +26,11 @@
  *     stream) and return without synchronising.
  *   - Arguments are validated on the host before anything is launched; a
  *     failed validation launches nothing.  A launch failure is SPEC_EHIP.
+ *     What only the device can see (lengths, block-table entries and draft
+ *     tokens in device memory) is checked again by the kernels: an entry out of
+ *     range is never used as an address, the request or test it belongs to is
+ *     skipped or rejected, and the count of such findings is reported (see
+ *     error_count and counters[6]).
  *   - Same inputs and same (philox_seed, philox_step) give the same outputs.
  *   - Limits: k_b <= SPEC_K_MAX, block_size == 16, d in {64, 128},
  *     Hq % Hkv == 0, Hq/Hkv <= 16, kv_len[b] >= q_len[b] >= 1.
@@ -92,8 +97,26 @@ typedef struct {
     const int32_t *cu_q_len;    /* [B+1] exclusive prefix sum of q_len */
     float softmax_scale;        /* 0 means 1/sqrt(d) */
     float *out;                 /* [T][Hq][d] fp32 */
-    const int32_t *host_kv_len;   /* HOST copy of kv_len, used to plan the split over the KV length */
+    const int32_t *host_kv_len;   /* HOST copy of kv_len, used to plan the split over the KV length
+                                     (may be NULL if max_kv_len > 0) */
     const int32_t *host_cu_q_len; /* HOST copy of cu_q_len */
+    /* Everything below may be zero / NULL. */
+    int32_t max_kv_len;         /* Length bucket.  0: the launch is planned from host_kv_len and is valid for
+                                   exactly those lengths.  > 0: the plan (split of the KV length, grid,
+                                   workspace size) depends on the shapes, host_cu_q_len and this bound only;
+                                   the kernels take the actual lengths from the device-side kv_len, so one
+                                   captured launch (HIP graph) stays valid while the lengths change from
+                                   step to step, as long as q_len[b] <= kv_len[b] <= max_kv_len.  host_kv_len,
+                                   if given, is then only a hint (order of the work items) and is checked
+                                   against the bound. */
+    int32_t validate;           /* 1: also check host_block_table (if given) on the host: every entry of a
+                                   page in use must be in [0, num_blocks), else SPEC_EINVAL */
+    const int32_t *host_block_table; /* optional HOST copy of block_table, read only when validate == 1 */
+    int64_t *error_count;       /* optional DEVICE counter [1], ADDED to: findings of the device-side checks
+                                   (a request whose kv_len is below its q_len, above the planned bound or
+                                   beyond its block-table row; a block-table entry outside [0, num_blocks)).
+                                   Such a request's output rows are not written; a bad page reads as zeros.
+                                   In spec_verify_step a NULL here means &reject->counters[6]. */
 } spec_attn_args;
 
 /*
@@ -144,8 +167,9 @@ typedef struct {
     const int32_t *host_cu_q_len; /* HOST copy (validation and launch planning) */
     uint64_t philox_seed;
     uint64_t philox_step;
-    int32_t *accepted_len;        /* [B] out: m_b in [0, k_b] (draft tokens only, bonus not counted) */
-    int32_t *next_token;          /* [B] out: correction or bonus token */
+    int32_t *accepted_len;        /* [B] out: m_b in [0, k_b] (draft tokens only, bonus not counted);
+                                     -1 for a request counted in counters[7] */
+    int32_t *next_token;          /* [B] out: correction or bonus token; -1 for a request counted in counters[7] */
     int32_t *out_tokens;          /* optional [B][SPEC_K_MAX+1]: accepted tokens, next token, -1 padding */
     int64_t *counters;            /* [SPEC_NUM_COUNTERS], ADDED to (caller zeroes):
                                      [0] proposed  sum k_b
@@ -154,7 +178,12 @@ typedef struct {
                                      [3] emitted   sum (m_b+1)          (goodput numerator, Eq. 1)
                                      [4] near ties: evaluated accept tests with |u - p/q| < 1e-6
                                      [5] requests
-                                     [6],[7] reserved, untouched */
+                                     [6] findings of the device-side input checks: draft tokens outside
+                                         [0, V) (such a token is rejected, never used as an index) and, in
+                                         spec_verify_step, the attention half's findings (see error_count)
+                                     [7] requests abandoned because a bounded wait inside the launch ran out
+                                         (never in a healthy launch): all their outputs are -1 and they are
+                                         not counted in [0]..[5] */
     double *debug_u_ratio;        /* optional [T-B][2]: u and p/q of each evaluated accept test, NaN otherwise */
     int32_t accept_mode;          /* spec_accept_mode */
     /* Cache bookkeeping after acceptance (Section 5.1, "KV Cache of Bonus Tokens"); all three
@@ -164,6 +193,13 @@ typedef struct {
                                      token is not in the cache yet (it is the next step's first query) */
     int32_t *draft_next_len;      /* [B] out: tokens the draft model's cache is behind by: 2 after full
                                      acceptance of k_b > 0 tokens (last draft token + bonus), else 1 */
+    /* Everything below may be zero / NULL. */
+    const uint64_t *philox_step_device; /* DEVICE [1]: if not NULL the step counter is read from here when the
+                                     kernels run and philox_step is ignored, so that a captured launch draws
+                                     fresh random numbers on every replay (the caller advances the word) */
+    int32_t validate;             /* 1: also check host_draft_tokens (if given) on the host: SPEC_EINVAL if a
+                                     token is outside [0, V) */
+    const int32_t *host_draft_tokens; /* optional HOST copy of draft_tokens, read only when validate == 1 */
 } spec_reject_args;
 
 /* Host-only: bytes of workspace the three calls below need for these shapes
@@ -203,6 +239,34 @@ spec_status spec_verify_step(const spec_attn_args *attn, const spec_reject_args 
 #define SPEC_STATIC_SCRATCH_BYTES (16u << 20)
 spec_status spec_verify_step_static(const spec_attn_args *attn, const spec_reject_args *reject, void *hip_stream);
 
+/*
+ * Host-only: how the library would run this step (either argument may be NULL), for
+ * callers and tests that want to know which kernel a shape takes.
+ */
+#define SPEC_PATH_NONE 0
+#define SPEC_PATH_MFMA 1     /* matrix-instruction attention inside the one-launch step kernel */
+#define SPEC_PATH_GENERIC 2  /* scalar attention kernel + merge kernel (fp32, token-major pages, d = 64) */
+typedef struct {
+    int32_t attn_path;       /* SPEC_PATH_* */
+    int32_t row_tiles;       /* 16-row tiles of query rows per attention block (matrix path) */
+    int32_t row_groups;      /* attention blocks that share the page stream of one (request, KV head, chunk):
+                                more than 48 fused rows per KV head are spread over several blocks placed
+                                on the same XCD, so that the second reader finds the pages in its L2 */
+    int32_t chunk_tokens;    /* bound of the tokens per chunk of the split over the KV length */
+    int32_t max_chunks;      /* chunks of the longest request the plan allows for */
+    int32_t launches;        /* kernel launches of the step */
+    int32_t early_stop;      /* 1: statistics in position order, rows after a first rejection unread */
+    int32_t stat_segments, race_segments;
+    int32_t attn_blocks, reject_blocks;
+    int32_t reserved;
+    uint64_t workspace_bytes;
+} spec_plan_info;
+spec_status spec_verify_plan(const spec_attn_args *attn, const spec_reject_args *reject, spec_plan_info *info);
+
+/* The tuning switches of the planner (environment variables SPEC_VERIFY_*) are read once, at
+ * the first call; this re-reads them (for sweeps and tests that change them in-process). */
+void spec_verify_reload_env(void);
+
 /* Host-only validation, exactly what the calls above run first. */
 spec_status spec_validate_attn(const spec_attn_args *attn);
 spec_status spec_validate_reject(const spec_reject_args *reject);
@@ -226,6 +290,9 @@ typedef struct {
     const int32_t *kv_len;        /* [B], INCLUDING the rows being appended */
     const int32_t *cu_q_len;      /* [B+1] */
     const int32_t *host_kv_len, *host_cu_q_len;
+    int64_t *error_count;         /* optional DEVICE counter [1], ADDED to: rows not written because the
+                                     device-side position fell outside the block-table row or its page
+                                     index outside [0, num_blocks) */
 } spec_kv_append_args;
 spec_status spec_kv_append(const spec_kv_append_args *args, void *hip_stream);
 

@@ -73,6 +73,12 @@ __global__ __launch_bounds__(kChunkThreads) void attn_generic_kernel(AttnParams 
     const int q_len = p.cu_q_len[b + 1] - p.cu_q_len[b];
     const int j = row - p.cu_q_len[b];
     const int L = p.kv_len[b];
+    // (lengths from device memory bound the loops and indices below: a request that does not fit
+    // the launch is left out and reported once)
+    if (!request_lengths_ok(L, q_len, p.capacity_tokens, p.max_blocks_per_req)) {
+        if (chunk == 0 && h == 0 && j == 0 && tid == 0 && p.errors != nullptr) atomicAdd(p.errors, 1ull);
+        return;
+    }
     const int nchunks = (L + p.chunk_tokens - 1) / p.chunk_tokens;
     if (chunk >= nchunks) return;
     const int last_visible = L - q_len + j;
@@ -94,14 +100,21 @@ __global__ __launch_bounds__(kChunkThreads) void attn_generic_kernel(AttnParams 
     const int token = chunk * p.chunk_tokens + tid;
     const bool visible = tid < p.chunk_tokens && token <= last_visible;
     float score = -INFINITY;
-    int page = 0;
+    int page = -1;
     if (visible) {
         page = p.block_table[(size_t)b * p.max_blocks_per_req + token / SPEC_BLOCK_SIZE];
         const int slot = token % SPEC_BLOCK_SIZE;
-        float dot = 0.0f;
-        for (int c = 0; c < d; ++c)
-            dot = fmaf(sh_q[c], load_as_float(kc, k_index(p.kv_layout, page, p.Hkv, kvh, slot, c, d)), dot);
-        score = dot * p.scale_log2;
+        if ((unsigned)page < (unsigned)p.num_blocks) {
+            float dot = 0.0f;
+            for (int c = 0; c < d; ++c)
+                dot = fmaf(sh_q[c], load_as_float(kc, k_index(p.kv_layout, page, p.Hkv, kvh, slot, c, d)), dot);
+            score = dot * p.scale_log2;
+        } else {
+            // an entry outside the pool is never turned into an address: the page reads as zeros
+            page = -1;
+            score = 0.0f;
+            if (slot == 0 && h == 0 && j == 0 && p.errors != nullptr) atomicAdd(p.errors, 1ull);
+        }
     }
     sh_page[tid] = page;
 
@@ -130,7 +143,8 @@ __global__ __launch_bounds__(kChunkThreads) void attn_generic_kernel(AttnParams 
         float acc = 0.0f;
         for (int t = 0; t < ntok; ++t) {
             const int slot = (chunk * p.chunk_tokens + t) % SPEC_BLOCK_SIZE;
-            acc = fmaf(sh_p[t], load_as_float(vc, v_index(p.kv_layout, sh_page[t], p.Hkv, kvh, slot, tid, d)), acc);
+            if (sh_page[t] >= 0)
+                acc = fmaf(sh_p[t], load_as_float(vc, v_index(p.kv_layout, sh_page[t], p.Hkv, kvh, slot, tid, d)), acc);
         }
         p.ws_acc[slot_index * d + tid] = acc;
     }
@@ -147,6 +161,8 @@ __global__ void attn_combine_kernel(AttnParams p)
     const int h = blockIdx.x % p.Hq;
     const int tid = threadIdx.x;
     const int b = find_request(p.cu_q_len, p.B, row);
+    if (!request_lengths_ok(p.kv_len[b], p.cu_q_len[b + 1] - p.cu_q_len[b], p.capacity_tokens, p.max_blocks_per_req))
+        return;   // left out by the partial kernel too
     const int nchunks = (p.kv_len[b] + p.chunk_tokens - 1) / p.chunk_tokens;
     if (nchunks == 1 && p.single_chunk_direct) return;
     const size_t base = ((size_t)row * p.Hq + h) * p.max_chunks;
@@ -194,7 +210,15 @@ __global__ void kv_append_kernel(KvAppendParams p)
     const int b = find_request(p.cu_q_len, p.B, row);
     const int q_len = p.cu_q_len[b + 1] - p.cu_q_len[b];
     const int pos = p.kv_len[b] - q_len + (row - p.cu_q_len[b]);
-    const int page = p.block_table[(size_t)b * p.max_blocks_per_req + pos / SPEC_BLOCK_SIZE];
+    // position and page index come from device memory: a row that would land outside the
+    // request's block-table row or outside the pool is not written, and counted
+    int page = -1;
+    if (pos >= 0 && pos / SPEC_BLOCK_SIZE < p.max_blocks_per_req)
+        page = p.block_table[(size_t)b * p.max_blocks_per_req + pos / SPEC_BLOCK_SIZE];
+    if ((unsigned)page >= (unsigned)p.num_blocks) {
+        if (g == 0 && kvh == 0 && p.errors != nullptr) atomicAdd(p.errors, 1ull);
+        return;
+    }
     const int slot = pos % SPEC_BLOCK_SIZE;
     const T *sk = static_cast<const T *>(p.new_k) + ((size_t)row * p.Hkv + kvh) * p.d + g * 8;
     const T *sv = static_cast<const T *>(p.new_v) + ((size_t)row * p.Hkv + kvh) * p.d + g * 8;

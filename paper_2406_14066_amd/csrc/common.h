@@ -32,7 +32,9 @@ struct AttnPlan {
     int32_t max_chunks;
     int32_t max_q_len;
     int32_t use_mfma;      // 1: bf16 matrix-instruction kernel, 0: generic kernel
-    int32_t row_tiles;     // 16-row tiles covering max_q_len * (Hq/Hkv) rows (mfma kernel)
+    int32_t row_tiles;     // 16-row tiles of query rows per attention block (mfma kernel, 1..3)
+    int32_t row_groups;    // blocks that share one (request, KV head, chunk): row_groups * row_tiles tiles cover max_q_len * (Hq/Hkv) rows
+    int32_t capacity_tokens;  // longest kv_len the plan allows for (chunk_tokens * max_chunks, capped by the bucket)
     int32_t fused_combine; // mfma kernel merges the chunk partials itself (few chunks) or leaves it to the combine kernel
     size_t acc_bytes;
     size_t ml_bytes;
@@ -55,15 +57,25 @@ struct AttnParams {
     int32_t single_chunk_direct;  // requests with one chunk were written straight to `out`: the combine kernel skips them
     int32_t reject_even_xcds;     // fused step: rejection blocks only at even positions of the grid's rows of 8 (see GridSplit)
     int32_t reject_even_limit;    // ... when there are at most this many attention blocks (the number of compute units)
+    int32_t capacity_tokens;      // a request whose device-side kv_len exceeds this is skipped and counted in *errors
+    int32_t row_groups;           // see AttnPlan
     int32_t reserved;
     const void *q, *k_cache, *v_cache;
     const int32_t *block_table, *kv_len, *cu_q_len;
     float *out;
     float *ws_acc;
     float *ws_ml;
-    unsigned long long *tickets;
+    unsigned long long *tickets;  // [B * Hkv * row_groups]
+    unsigned long long *errors;   // findings of the device-side input checks are added here (may be null)
 };
-static_assert(sizeof(AttnParams) == 20 * 4 + 10 * 8, "AttnParams has padding");
+static_assert(sizeof(AttnParams) == 22 * 4 + 11 * 8, "AttnParams has padding");
+
+// What the kernels check of a request before they use its lengths as loop bounds and indices.
+__host__ __device__ inline bool request_lengths_ok(int kv_len, int q_len, int capacity_tokens, int max_blocks_per_req)
+{
+    return q_len >= 1 && q_len <= SPEC_K_MAX + 1 && kv_len >= q_len && kv_len <= capacity_tokens &&
+           (kv_len + SPEC_BLOCK_SIZE - 1) / SPEC_BLOCK_SIZE <= max_blocks_per_req;
+}
 
 // ---------------------------------------------------------------- rejection
 // Records handed between the rejection stages are arrays of 8-byte words, each a
@@ -105,8 +117,9 @@ struct RejectParams {
     unsigned long long *stats;           // [rows][stat_segments][3]
     unsigned long long *race_partial;    // [B][race_segments][2]
     unsigned long long *race_info;       // [B]
+    const unsigned long long *step_device;   // if not null: the Philox step counter, read when the kernel runs
 };
-static_assert(sizeof(RejectParams) == 16 * 4 + 15 * 8, "RejectParams has padding");
+static_assert(sizeof(RejectParams) == 16 * 4 + 16 * 8, "RejectParams has padding");
 
 // Order in which the attention items take the requests (longest first), passed as a
 // kernel argument.  n == 0: the given order.
@@ -124,7 +137,9 @@ struct LaunchEvents {
 };
 
 // One launch for the whole step (either half may be absent).  `attn` needs the
-// matrix-instruction path (bf16, SPEC_KV_MFMA, d = 128, row_tiles <= 3).  `order` may be null.
+// matrix-instruction path (bf16, SPEC_KV_MFMA, d = 128, row_tiles <= 3; ap.row_groups blocks per
+// (request, KV head, chunk)).  `order` may be null.
+int step_attn_items(const AttnParams &ap);   // attention blocks of the launch
 hipError_t launch_step_fused(const AttnParams *attn, int row_tiles, const RejectParams *reject, const UnitOrder *order,
                              LaunchEvents events, hipStream_t stream);
 
@@ -132,10 +147,11 @@ hipError_t launch_step_fused(const AttnParams *attn, int row_tiles, const Reject
 hipError_t launch_attn_generic(const AttnParams &p, int dtype, hipStream_t stream);
 hipError_t launch_attn_combine(const AttnParams &p, hipStream_t stream);
 struct KvAppendParams {
-    int32_t B, Hkv, d, max_blocks_per_req, T, kv_layout, elem_bytes;
+    int32_t B, Hkv, d, max_blocks_per_req, T, kv_layout, elem_bytes, num_blocks;
     const void *new_k, *new_v;
     void *k_cache, *v_cache;
     const int32_t *block_table, *kv_len, *cu_q_len;
+    unsigned long long *errors;   // rows skipped by the device-side checks are counted here (may be null)
 };
 hipError_t launch_kv_append(const KvAppendParams &p, hipStream_t stream);
 hipError_t launch_kv_repack(const void *src_k, const void *src_v, void *dst_k, void *dst_v, int32_t num_blocks,

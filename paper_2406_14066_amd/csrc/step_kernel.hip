@@ -73,6 +73,7 @@ constexpr int kBufferFlags = 0x00020000;   // raw 32-bit buffer descriptor, word
 // words); measured on the four large workloads the hint alone takes 8-10% off the step.
 constexpr int kStreamPolicy = 2;           // "nt" bit of a raw buffer load
 constexpr float kRescaleSlack = 8.0f;      // see the online softmax of the attention role
+constexpr int kXcds = 8;                   // the hardware deals consecutive blocks of a grid to the 8 XCDs in turn
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
@@ -207,6 +208,23 @@ __device__ __forceinline__ uint4 philox4x32_10(uint4 c, uint32_t k0, uint32_t k1
         k1 += 0xBB67AE85u;
     }
     return c;
+}
+
+// The step counter of the random numbers: the launch's own, or, if the caller gave a device word
+// (a captured launch that draws fresh numbers on every replay), what that word holds now.
+struct StepWords {
+    uint32_t lo, hi24;
+};
+typedef const unsigned long long __attribute__((address_space(4))) *uniform_u64_ptr;
+__device__ __forceinline__ StepWords philox_step_words(const RejectParams &p)
+{
+    StepWords w = {p.step_lo, p.step_hi24};
+    if (p.step_device != nullptr) {
+        const unsigned long long s = *((uniform_u64_ptr)(uintptr_t)p.step_device);
+        w.lo = (uint32_t)s;
+        w.hi24 = (uint32_t)(s >> 32) & 0xFFFFFFu;
+    }
+    return w;
 }
 
 constexpr int kMaxStatSegments = 32;
@@ -378,7 +396,8 @@ __device__ __forceinline__ void race_segment(const RejectParams &p, const float 
     float best_score = -1.0f;
     int best_id = 0x7FFFFFFF;
     const int g_begin = v0 >> 2, g_end = v1 >> 2;
-    const uint32_t c3 = (p.step_hi24 << 8) | 1u;
+    const StepWords step = philox_step_words(p);
+    const uint32_t c3 = (step.hi24 << 8) | 1u;
     constexpr int U = 8;  // row vectors in flight per thread
     for (int g0 = g_begin + threadIdx.x; g0 < g_end; g0 += kThreads * U) {
         float4 xt[U], xd[U];
@@ -407,7 +426,7 @@ __device__ __forceinline__ void race_segment(const RejectParams &p, const float 
                 for (int e = 0; e < 4; ++e)
                     r[e] -= corr_d * fast_exp2(fmaf(x[e], kLog2eHi, fmaf(x[e], kLog2eLo, off_d)));
             }
-            const uint4 w = philox4x32_10(make_uint4((uint32_t)g, (uint32_t)b, p.step_lo, c3), p.seed_lo, p.seed_hi);
+            const uint4 w = philox4x32_10(make_uint4((uint32_t)g, (uint32_t)b, step.lo, c3), p.seed_lo, p.seed_hi);
             const uint32_t word[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -474,11 +493,15 @@ __device__ __forceinline__ bool accept_phase(const RejectParams &p, int b, Rejec
     const int npos_eval = npos < 0 ? k : npos;
 
     // the draft tokens' logits do not depend on the statistics: fetch them first
-    float tx = 0.0f, dx = 0.0f;
+    // (a token outside the vocabulary is never used as an index: it has probability 0 under the
+    // target, so its test rejects; the final stage counts it among the input errors)
+    float tx = -INFINITY, dx = 0.0f;
     if (tid < npos_eval) {
         const int x = p.draft_tokens[row_d0 + tid];
-        tx = p.target_logits[(size_t)(row_t0 + tid) * p.V + x];
-        if (has_draft_rows) dx = p.draft_logits[(size_t)(row_d0 + tid) * p.V + x];
+        if ((unsigned)x < (unsigned)p.V) {
+            tx = p.target_logits[(size_t)(row_t0 + tid) * p.V + x];
+            if (has_draft_rows) dx = p.draft_logits[(size_t)(row_d0 + tid) * p.V + x];
+        }
     }
 
     // poll and fetch in one: every word carries its own tag
@@ -513,7 +536,8 @@ __device__ __forceinline__ bool accept_phase(const RejectParams &p, int b, Rejec
         const double log2_p = (double)tx * kLog2eD - sh.lse2[tid];
         const double log2_q = has_draft_rows ? (double)dx * kLog2eD - sh.lse2[k + 1 + tid] : 0.0;   // point mass: q(x) = 1
         const double ratio = exp2(log2_p - log2_q);  // p = 0 -> 0, q = 0 < p -> inf, both 0 -> NaN (rejects)
-        const uint4 w = philox4x32_10(make_uint4((uint32_t)tid, (uint32_t)b, p.step_lo, (p.step_hi24 << 8) | 0u),
+        const StepWords step = philox_step_words(p);
+        const uint4 w = philox4x32_10(make_uint4((uint32_t)tid, (uint32_t)b, step.lo, (step.hi24 << 8) | 0u),
                                       p.seed_lo, p.seed_hi);
         const double u = (double)(w.x >> 8) * (1.0 / 16777216.0);
         sh.u[tid] = u;
@@ -657,6 +681,29 @@ __device__ __forceinline__ void stats_role(const RejectParams &p, int item, Reje
     stats_block<UNROLL>(p, row, seg, sh);
 }
 
+// A request whose bounded wait ran out (never in a healthy launch): every output gets its
+// sentinel and the request is counted in counters[7] only.
+__device__ __forceinline__ void abandon_request(const RejectParams &p, int b)
+{
+    const int tid = threadIdx.x;
+    if (p.out_tokens != nullptr && tid <= SPEC_K_MAX) p.out_tokens[(size_t)b * (SPEC_K_MAX + 1) + tid] = -1;
+    if (tid != 0) return;
+    p.accepted_len[b] = -1;
+    p.next_token[b] = -1;
+    if (p.new_kv_len != nullptr) p.new_kv_len[b] = -1;
+    if (p.draft_next_len != nullptr) p.draft_next_len[b] = -1;
+    atomicAdd(&p.counters[7], 1ull);
+}
+
+// Draft tokens of request b outside [0, V): counted among the input errors (counters[6]).
+__device__ __forceinline__ void count_bad_draft_tokens(const RejectParams &p, int row_d0, int k)
+{
+    int bad = 0;
+    for (int i = 0; i < k; ++i)
+        if ((unsigned)p.draft_tokens[row_d0 + i] >= (unsigned)p.V) ++bad;
+    if (bad) atomicAdd(&p.counters[6], (unsigned long long)bad);
+}
+
 // Offsets of the race rows of request b after accept_phase.
 struct RaceRows {
     const float *trow, *drow;
@@ -693,16 +740,14 @@ __device__ __forceinline__ RaceRows race_rows(const RejectParams &p, int b, cons
 // One (request, vocabulary segment) of the race.  Race items follow all statistics
 // items in the grid, so the statistics blocks they wait for (inside accept_phase, with
 // a bound) were scheduled before them and never wait themselves: the wait ends.
-// Should the bound ever run out, the request's outputs are set to -1.
+// Should the bound ever run out, the block publishes nothing and the request's final stage,
+// whose own wait then runs out too, abandons the request.
 __device__ __forceinline__ void race_role(const RejectParams &p, int item, RejectShared &sh)
 {
     const int tid = threadIdx.x;
     const int b = item / p.race_segments;
     const int seg = item - b * p.race_segments;
-    if (!accept_phase(p, b, sh, seg == 0)) {
-        if (tid == 0 && seg == 0) { p.accepted_len[b] = -1; p.next_token[b] = -1; }
-        return;
-    }
+    if (!accept_phase(p, b, sh, seg == 0)) return;
     const RaceRows rr = race_rows(p, b, sh);
     const int v0 = seg * p.race_seg_len;
     const int v1 = min(p.V, v0 + p.race_seg_len);
@@ -744,7 +789,7 @@ __device__ __forceinline__ void greedy_final(const RejectParams &p, int b, Rejec
         return mine;
     });
     if (!ok) {
-        if (tid == 0) { p.accepted_len[b] = -1; p.next_token[b] = -1; }
+        abandon_request(p, b);
         return;
     }
     if (tid <= k) {
@@ -776,6 +821,7 @@ __device__ __forceinline__ void greedy_final(const RejectParams &p, int b, Rejec
         atomicAdd(&p.counters[2], (unsigned long long)(m + 1 < k ? m + 1 : k));
         atomicAdd(&p.counters[3], (unsigned long long)(m + 1));
         atomicAdd(&p.counters[5], 1ull);
+        count_bad_draft_tokens(p, row_d0, k);
     }
     // clear this request's tags
     for (int i = tid; i < 2 * nstat; i += kThreads) {
@@ -817,7 +863,7 @@ __device__ __forceinline__ void final_role(const RejectParams &p, int b, RejectS
         return mine;
     });
     if (!ok) {
-        if (tid == 0) { p.accepted_len[b] = -1; p.next_token[b] = -1; }
+        abandon_request(p, b);
         return;
     }
     if (tid == 0) sh.m = (int)info;
@@ -839,7 +885,7 @@ __device__ __forceinline__ void final_role(const RejectParams &p, int b, RejectS
     if (!(win_score > 0.0f)) {
         // p - q has no positive entry (p == q to rounding): draw from p instead
         if (!accept_phase(p, b, sh, false)) {
-            if (tid == 0) { p.accepted_len[b] = -1; p.next_token[b] = -1; }
+            abandon_request(p, b);
             return;
         }
         const RaceRows rr = race_rows(p, b, sh);
@@ -861,6 +907,7 @@ __device__ __forceinline__ void final_role(const RejectParams &p, int b, RejectS
         atomicAdd(&p.counters[3], (unsigned long long)(m + 1));
         atomicAdd(&p.counters[4], (unsigned long long)near);
         atomicAdd(&p.counters[5], 1ull);
+        count_bad_draft_tokens(p, row_d0, k);
     }
     // clear this request's tags
     const int nstat = (p.mode == SPEC_ACCEPT_SAMPLE ? 2 * k + 1 : k + 1) * p.stat_segments;
@@ -926,10 +973,29 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
     // gets the same mix of chunk indices; the chunk indices that only the longest requests
     // have come last (blocks of the others for these indices exit at once), instead of
     // always falling on the same XCDs.
+    // With more than three row tiles per KV head (row_groups > 1) the rows of a (request, KV
+    // head, chunk) are spread over row_groups blocks of up to NT tiles each.  They sit 8 items
+    // apart, i.e. on the same XCD and dispatched one right after the other, so that the pages
+    // the first of them pulls from memory are found in that XCD's L2 by the others: K and V
+    // still cross the memory interface once.
     const int n_units = p.B * p.Hkv;
-    const int chunk = item / n_units;
-    const int kvh = (item % n_units) % p.Hkv;
-    int b = (item % n_units) / p.Hkv;   // rank in the order of the attention items
+    int chunk, kvh, b, rg = 0;   // b: rank in the order of the attention items
+    if (p.row_groups > 1) {
+        const int unit_rows = (n_units + kXcds - 1) / kXcds;
+        const int col = item % kXcds;
+        int t = item / kXcds;
+        rg = t % p.row_groups;
+        t /= p.row_groups;
+        const int urank = (t % unit_rows) * kXcds + col;
+        chunk = t / unit_rows;
+        if (urank >= n_units) return;   // padding of the last row of units
+        kvh = urank % p.Hkv;
+        b = urank / p.Hkv;
+    } else {
+        chunk = item / n_units;
+        kvh = (item % n_units) % p.Hkv;
+        b = (item % n_units) / p.Hkv;
+    }
     if (order.n > 0) {
         const uint32_t pair = order.pairs[b >> 1];
         b = (int)((b & 1) ? pair >> 16 : pair & 0xFFFFu);
@@ -942,14 +1008,23 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
     if (p.max_chunks == 1 && wave + kWaves * lane < p.max_blocks_per_req)
         bt = p.block_table[(size_t)b * p.max_blocks_per_req + wave + kWaves * lane];
     const int L = uniform_load(p.kv_len, b);
-    const int nchunks = (L + p.chunk_tokens - 1) / p.chunk_tokens;
+    const int row0 = uniform_load(p.cu_q_len, b);
+    const int q_len = uniform_load(p.cu_q_len, b + 1) - row0;
+    // The lengths come from device memory and bound every loop and index below: a request
+    // whose lengths do not fit the launch (longer than planned for, beyond its block-table row,
+    // shorter than its own query rows) is left out and reported.
+    if (!request_lengths_ok(L, q_len, p.capacity_tokens, p.max_blocks_per_req)) {
+        if (chunk == 0 && kvh == 0 && rg == 0 && tid == 0 && p.errors != nullptr) atomicAdd(p.errors, 1ull);
+        return;
+    }
+    const int nchunks = (L + p.chunk_tokens - 1) / p.chunk_tokens;   // <= max_chunks, since L <= capacity_tokens
     if (chunk >= nchunks) return;
     // even chunks per request, page aligned (never longer than chunk_tokens)
     const int C = ((L + nchunks - 1) / nchunks + SPEC_BLOCK_SIZE - 1) & ~(SPEC_BLOCK_SIZE - 1);
-    const int row0 = uniform_load(p.cu_q_len, b);
-    const int q_len = uniform_load(p.cu_q_len, b + 1) - row0;
     const int group = p.Hq / p.Hkv;
-    const int rows = q_len * group;
+    const int row_lo = rg * (NT * 16);           // first of this block's rows among the q_len * group rows
+    if (row_lo >= q_len * group) return;         // this request has no rows for this row group
+    const int rows = min(q_len * group - row_lo, NT * 16);
     const int tok0 = chunk * C;
     const int tok1 = min(L, tok0 + C);
     const int npages = (tok1 - tok0 + SPEC_BLOCK_SIZE - 1) / SPEC_BLOCK_SIZE;  // <= 256
@@ -958,6 +1033,14 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
     // block-table entries of this wavefront's pages (wave, wave+4, ...), one per lane
     if (p.max_chunks != 1 && wave + kWaves * lane < npages)
         bt = p.block_table[(size_t)b * p.max_blocks_per_req + page0 + wave + kWaves * lane];
+    {
+        // an entry outside the pool is never turned into an address: the page reads as zeros
+        const bool bad = wave + kWaves * lane < npages && (unsigned)bt >= (unsigned)p.num_blocks;
+        if (bad) bt = -1;
+        const unsigned long long bad_lanes = __builtin_amdgcn_ballot_w64(bad);
+        if (bad_lanes != 0 && kvh == 0 && rg == 0 && p.errors != nullptr && lane == 0)
+            atomicAdd(p.errors, (unsigned long long)__builtin_popcountll(bad_lanes));
+    }
 
     // Q: the block fetches its query rows once, 16 bytes per thread and consecutive threads
     // along a row (the heads of a group are adjacent in memory), and leaves them in LDS
@@ -968,7 +1051,7 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
         const int r = piece >> 4, c = piece & 15;
         qpiece[i] = (u32x4){0u, 0u, 0u, 0u};
         if (r < rows) {
-            const size_t rh = (size_t)(row0 + r / group) * p.Hq + kvh * group + r % group;
+            const size_t rh = (size_t)(row0 + (row_lo + r) / group) * p.Hq + kvh * group + (row_lo + r) % group;
             qpiece[i] = *reinterpret_cast<const u32x4 *>(static_cast<const char *>(p.q) + rh * (kD * 2) + c * 16);
         }
     }
@@ -979,8 +1062,8 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
     for (int nt = 0; nt < NT; ++nt) {
         const int r = nt * 16 + n16;
         const bool valid = r < rows;
-        const int j = valid ? r / group : 0;
-        const int gq = valid ? r % group : 0;
+        const int j = valid ? (row_lo + r) / group : 0;
+        const int gq = valid ? (row_lo + r) % group : 0;
         limit[nt] = valid ? L - q_len + j : -1;
         out_row[nt] = valid ? (int)((size_t)(row0 + j) * p.Hq + kvh * group + gq) : -1;
     }
@@ -998,8 +1081,9 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
     const int lane_off = lane * 16;
 
     auto load_page = [&](int it, PageRegs &r) {   // it-th page of this wavefront
-        const bool valid = it < my_pages;
-        const int page = __builtin_amdgcn_readlane(bt, valid ? it : 0);
+        const int entry = __builtin_amdgcn_readlane(bt, it < my_pages ? it : 0);
+        const bool valid = it < my_pages && entry >= 0;
+        const int page = valid ? entry : 0;
         const int bytes = valid ? kPageHeadBytes : 0;
         const __amdgpu_buffer_rsrc_t kd = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<char *>(khead + (size_t)page * page_stride), 0, bytes, kBufferFlags);
@@ -1193,7 +1277,7 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
         __syncthreads();
         for (int piece = tid; piece < rows * 32; piece += kThreads) {   // 32 pieces per row
             const int r = piece >> 5, c = piece & 31;
-            const size_t rh = (size_t)(row0 + r / group) * p.Hq + kvh * group + r % group;
+            const size_t rh = (size_t)(row0 + (row_lo + r) / group) * p.Hq + kvh * group + (row_lo + r) % group;
             __builtin_nontemporal_store(*reinterpret_cast<const f32x4 *>(sh.o + r * kOStride + c * 16),
                                         reinterpret_cast<f32x4 *>(p.out + rh * kD + c * 4));
         }
@@ -1219,7 +1303,7 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
         if (!p.fused_combine) return;   // a separate combine launch merges the partials
         writes_complete();  // the partial is in memory before the ticket is taken
         if (lane == 0) {
-            unsigned long long *ticket = &p.tickets[unit];
+            unsigned long long *ticket = &p.tickets[(size_t)unit * p.row_groups + rg];
             const uint32_t before = ticket_arrive(ticket, p.generation);
             const int last = (before + 1u == (uint32_t)nchunks) ? 1 : 0;
             if (last) ticket_reset(ticket);
@@ -1248,7 +1332,7 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
         for (int j = 0; j < RB; ++j) {
             const int r = r0 + 2 * kWaves * j;
             rv[j] = r < rows;
-            const int rr = rv[j] ? r : 0;
+            const int rr = row_lo + (rv[j] ? r : 0);
             rh[j] = (size_t)(row0 + rr / group) * p.Hq + kvh * group + rr % group;
             const size_t base = rh[j] * p.max_chunks;
             ml[j] = reinterpret_cast<const unsigned long long *>(p.ws_ml) + base;
@@ -1315,8 +1399,6 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
 //    alias with that (with equal counts, "every other block" would put all attention on
 //    four XCDs and all rejection on the other four).  Within the mixed part, row r is an
 //    attention row iff floor((r+1) * rows_attn / rows) > floor(r * rows_attn / rows).
-constexpr int kXcds = 8;
-
 struct GridSplit {
     int n_stat, n_reject, n_attn;
     int attn_first;
@@ -1460,6 +1542,13 @@ hipError_t launch(const AttnParams &ap, const RejectParams &rp, int n_stat, int 
 
 }  // namespace
 
+int step_attn_items(const AttnParams &ap)
+{
+    const int n_units = ap.B * ap.Hkv;
+    if (ap.row_groups > 1) return (n_units + kXcds - 1) / kXcds * kXcds * ap.row_groups * ap.max_chunks;
+    return n_units * ap.max_chunks;
+}
+
 hipError_t launch_step_fused(const AttnParams *attn, int row_tiles, const RejectParams *reject, const UnitOrder *order,
                              LaunchEvents ev, hipStream_t stream)
 {
@@ -1477,9 +1566,10 @@ hipError_t launch_step_fused(const AttnParams *attn, int row_tiles, const Reject
     if (attn != nullptr) {
         ap = *attn;
         if (ap.d != kD || ap.chunk_tokens > 4096 || ap.chunk_tokens % SPEC_BLOCK_SIZE != 0 || row_tiles < 1 ||
-            row_tiles > 3 || (ap.fused_combine && ap.max_chunks > kMaxFusedChunks) || (order != nullptr && order->n != 0 && order->n != ap.B))
+            row_tiles > 3 || ap.row_groups < 1 || ap.capacity_tokens > ap.chunk_tokens * ap.max_chunks ||
+            (ap.fused_combine && ap.max_chunks > kMaxFusedChunks) || (order != nullptr && order->n != 0 && order->n != ap.B))
             return hipErrorInvalidValue;
-        n_attn = ap.B * ap.Hkv * ap.max_chunks;
+        n_attn = step_attn_items(ap);
     }
     if (attn == nullptr) return launch<1, false, true>(ap, rp, n_stat, 0, n_race, nullptr, ev, stream);
     if (reject == nullptr) {

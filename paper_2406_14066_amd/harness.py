@@ -20,11 +20,12 @@ class DeviceStep:
     """One verification step resident on the GPU."""
 
     def __init__(self, w: VerifyWorkload, kv_layout: int = sv.KV_TOKEN_MAJOR, device="cuda",
-                 with_debug: bool = True, accept_mode: int = sv.ACCEPT_SAMPLE):
+                 with_debug: bool = True, accept_mode: int = sv.ACCEPT_SAMPLE, max_kv_len: int = 0):
         self.w = w
         self.device = device
         self.kv_layout = kv_layout
         self.accept_mode = accept_mode
+        self.max_kv_len = max_kv_len
         self.q = _to_device_kv(w.q, device)
         k_tm = _to_device_kv(w.k_pages, device)
         v_tm = _to_device_kv(w.v_pages, device)
@@ -52,7 +53,7 @@ class DeviceStep:
                       if with_debug else None)
         self.attn_args, self._keep_a = sv.make_attn_args(
             self.q, self.k_cache, self.v_cache, self.block_table, self.kv_len, self.cu_q_len, self.out,
-            w.kv_len, w.cu_q_len, Hkv=w.Hkv, kv_layout=kv_layout)
+            w.kv_len, w.cu_q_len, Hkv=w.Hkv, kv_layout=kv_layout, max_kv_len=max_kv_len)
         self.reject_args, self._keep_r = sv.make_reject_args(
             self.target_logits, self.draft_logits, self.draft_tokens, self.cu_q_len, w.cu_q_len,
             self.accepted_len, self.next_token, self.counters, philox_seed=w.philox_seed,
@@ -72,7 +73,8 @@ class DeviceStep:
             tl = self.target_logits.clone()
             dl = self.draft_logits.clone() if self.draft_logits is not None else None
             a, keep_a = sv.make_attn_args(self.q, kc, vc, self.block_table, self.kv_len, self.cu_q_len, self.out,
-                                          w.kv_len, w.cu_q_len, Hkv=w.Hkv, kv_layout=self.kv_layout)
+                                          w.kv_len, w.cu_q_len, Hkv=w.Hkv, kv_layout=self.kv_layout,
+                                          max_kv_len=self.max_kv_len)
             r, keep_r = sv.make_reject_args(tl, dl, self.draft_tokens, self.cu_q_len, w.cu_q_len, self.accepted_len,
                                             self.next_token, self.counters, philox_seed=w.philox_seed,
                                             philox_step=w.philox_step, out_tokens=self.out_tokens,
@@ -80,6 +82,10 @@ class DeviceStep:
             pairs.append((a, r))
             self._rotated_keep.append((kc, vc, tl, dl, keep_a, keep_r))
         return pairs
+
+    def plan(self) -> dict:
+        """How the library runs this step (attention path, split, launches)."""
+        return sv.spec_verify_plan(self.attn_args, self.reject_args)
 
     def input_bytes(self) -> int:
         """Bytes of the big inputs (K and V pools, logits) of one copy."""

@@ -25,7 +25,7 @@ SPEC_F32, SPEC_BF16 = 0, 1
 KV_TOKEN_MAJOR, KV_MFMA = 0, 1
 ACCEPT_SAMPLE, ACCEPT_GREEDY, ACCEPT_POINT_DRAFT = 0, 1, 2   # spec_accept_mode
 
-COUNTER_NAMES = ("proposed", "accepted", "attempted", "emitted", "near_tie", "requests", "reserved6", "reserved7")
+COUNTER_NAMES = ("proposed", "accepted", "attempted", "emitted", "near_tie", "requests", "input_errors", "abandoned")
 
 
 class AttnArgs(C.Structure):
@@ -38,6 +38,8 @@ class AttnArgs(C.Structure):
         ("softmax_scale", C.c_float),
         ("out", C.c_void_p),
         ("host_kv_len", C.c_void_p), ("host_cu_q_len", C.c_void_p),
+        ("max_kv_len", C.c_int32), ("validate", C.c_int32),
+        ("host_block_table", C.c_void_p), ("error_count", C.c_void_p),
     ]
 
 
@@ -51,6 +53,7 @@ class RejectArgs(C.Structure):
         ("counters", C.c_void_p), ("debug_u_ratio", C.c_void_p),
         ("accept_mode", C.c_int32),
         ("kv_len", C.c_void_p), ("new_kv_len", C.c_void_p), ("draft_next_len", C.c_void_p),
+        ("philox_step_device", C.c_void_p), ("validate", C.c_int32), ("host_draft_tokens", C.c_void_p),
     ]
 
 
@@ -61,12 +64,29 @@ class KvAppendArgs(C.Structure):
         ("new_k", C.c_void_p), ("new_v", C.c_void_p), ("k_cache", C.c_void_p), ("v_cache", C.c_void_p),
         ("block_table", C.c_void_p), ("kv_len", C.c_void_p), ("cu_q_len", C.c_void_p),
         ("host_kv_len", C.c_void_p), ("host_cu_q_len", C.c_void_p),
+        ("error_count", C.c_void_p),
     ]
+
+
+class PlanInfo(C.Structure):
+    _fields_ = [
+        ("attn_path", C.c_int32), ("row_tiles", C.c_int32), ("row_groups", C.c_int32),
+        ("chunk_tokens", C.c_int32), ("max_chunks", C.c_int32), ("launches", C.c_int32),
+        ("early_stop", C.c_int32), ("stat_segments", C.c_int32), ("race_segments", C.c_int32),
+        ("attn_blocks", C.c_int32), ("reject_blocks", C.c_int32), ("reserved", C.c_int32),
+        ("workspace_bytes", C.c_uint64),
+    ]
+
+    def as_dict(self):
+        return {f: getattr(self, f) for f, _ in self._fields_ if f != "reserved"}
+
+
+PATH_NONE, PATH_MFMA, PATH_GENERIC = 0, 1, 2
 
 
 EXPORTS = (
     "spec_verify_workspace_bytes", "spec_verify_attn", "spec_reject_sample", "spec_verify_step",
-    "spec_verify_step_static",
+    "spec_verify_step_static", "spec_verify_plan", "spec_verify_reload_env",
     "spec_validate_attn", "spec_validate_reject", "spec_kv_repack_mfma", "spec_kv_append", "spec_status_string",
     "spec_verify_version", "spec_profile_begin", "spec_profile_end",
     "spec_expected_generated_len", "spec_predict_latency", "spec_fit_latency",
@@ -103,6 +123,10 @@ def lib():
         L.spec_verify_step.restype = C.c_int
         L.spec_verify_step_static.argtypes = [C.POINTER(AttnArgs), C.POINTER(RejectArgs), C.c_void_p]
         L.spec_verify_step_static.restype = C.c_int
+        L.spec_verify_plan.argtypes = [C.POINTER(AttnArgs), C.POINTER(RejectArgs), C.POINTER(PlanInfo)]
+        L.spec_verify_plan.restype = C.c_int
+        L.spec_verify_reload_env.argtypes = []
+        L.spec_verify_reload_env.restype = None
         L.spec_validate_attn.argtypes = [C.POINTER(AttnArgs)]
         L.spec_validate_attn.restype = C.c_int
         L.spec_validate_reject.argtypes = [C.POINTER(RejectArgs)]
@@ -146,7 +170,8 @@ def _stream_handle(stream) -> Optional[int]:
 
 def make_attn_args(q, k_cache, v_cache, block_table, kv_len, cu_q_len, out, host_kv_len, host_cu_q_len,
                    *, Hkv: int, kv_layout: int = KV_TOKEN_MAJOR, softmax_scale: float = 0.0,
-                   block_size: int = BLOCK_SIZE):
+                   block_size: int = BLOCK_SIZE, max_kv_len: int = 0, validate: int = 0, host_block_table=None,
+                   error_count=None):
     """Builds the argument struct from device tensors (torch) and host arrays (numpy).
     Returns (struct, keepalive) -- keep `keepalive` referenced while the struct is in use."""
     import torch
@@ -157,10 +182,11 @@ def make_attn_args(q, k_cache, v_cache, block_table, kv_len, cu_q_len, out, host
         dtype = SPEC_BF16
     else:
         raise TypeError("q must be float32 or bfloat16")
-    hk = _host_i32(host_kv_len)
+    hk = _host_i32(host_kv_len) if host_kv_len is not None else None
     hc = _host_i32(host_cu_q_len)
+    hb = _host_i32(host_block_table) if host_block_table is not None else None
     a = AttnArgs()
-    a.B = hk.shape[0]
+    a.B = hc.shape[0] - 1
     a.Hq, a.Hkv, a.d = Hq, Hkv, d
     a.block_size = block_size
     a.num_blocks = k_cache.shape[0]
@@ -172,15 +198,21 @@ def make_attn_args(q, k_cache, v_cache, block_table, kv_len, cu_q_len, out, host
     a.block_table, a.kv_len, a.cu_q_len = block_table.data_ptr(), kv_len.data_ptr(), cu_q_len.data_ptr()
     a.softmax_scale = softmax_scale
     a.out = out.data_ptr()
-    a.host_kv_len = hk.ctypes.data
+    a.host_kv_len = hk.ctypes.data if hk is not None else None
     a.host_cu_q_len = hc.ctypes.data
-    return a, (hk, hc, q, k_cache, v_cache, block_table, kv_len, cu_q_len, out)
+    a.max_kv_len = max_kv_len
+    a.validate = validate
+    a.host_block_table = hb.ctypes.data if hb is not None else None
+    a.error_count = _dev_ptr(error_count)
+    return a, (hk, hc, hb, q, k_cache, v_cache, block_table, kv_len, cu_q_len, out, error_count)
 
 
 def make_reject_args(target_logits, draft_logits, draft_tokens, cu_q_len, host_cu_q_len, accepted_len, next_token,
                      counters, *, philox_seed: int, philox_step: int, out_tokens=None, debug_u_ratio=None,
-                     accept_mode: int = 0, kv_len=None, new_kv_len=None, draft_next_len=None):
+                     accept_mode: int = 0, kv_len=None, new_kv_len=None, draft_next_len=None,
+                     philox_step_device=None, validate: int = 0, host_draft_tokens=None):
     hc = _host_i32(host_cu_q_len)
+    hd = _host_i32(host_draft_tokens) if host_draft_tokens is not None else None
     r = RejectArgs()
     r.B = hc.shape[0] - 1
     r.T, r.V = target_logits.shape
@@ -200,7 +232,10 @@ def make_reject_args(target_logits, draft_logits, draft_tokens, cu_q_len, host_c
     r.kv_len = _dev_ptr(kv_len)
     r.new_kv_len = _dev_ptr(new_kv_len)
     r.draft_next_len = _dev_ptr(draft_next_len)
-    return r, (hc, target_logits, draft_logits, draft_tokens, cu_q_len, accepted_len, next_token, counters,
+    r.philox_step_device = _dev_ptr(philox_step_device)
+    r.validate = validate
+    r.host_draft_tokens = hd.ctypes.data if hd is not None else None
+    return r, (hc, hd, philox_step_device, target_logits, draft_logits, draft_tokens, cu_q_len, accepted_len, next_token, counters,
                out_tokens, debug_u_ratio, kv_len, new_kv_len, draft_next_len)
 
 
@@ -210,6 +245,19 @@ def spec_verify_workspace_bytes(attn: Optional[AttnArgs], reject: Optional[Rejec
     if n == 0:
         raise SpecVerifyError(SPEC_EINVAL, "spec_verify_workspace_bytes")
     return int(n)
+
+
+def spec_verify_plan(attn: Optional[AttnArgs], reject: Optional[RejectArgs]) -> dict:
+    """How the library would run this step: which attention kernel, the split, the launches."""
+    info = PlanInfo()
+    _check(lib().spec_verify_plan(C.byref(attn) if attn is not None else None,
+                                  C.byref(reject) if reject is not None else None, C.byref(info)), "spec_verify_plan")
+    return info.as_dict()
+
+
+def reload_env() -> None:
+    """Re-reads the SPEC_VERIFY_* tuning switches (the library reads them once, at its first call)."""
+    lib().spec_verify_reload_env()
 
 
 def spec_validate_attn(attn: AttnArgs) -> int:
@@ -254,7 +302,7 @@ def spec_kv_repack_mfma(src_k, src_v, dst_k, dst_v, stream=None) -> None:
 
 
 def spec_kv_append(new_k, new_v, k_cache, v_cache, block_table, kv_len, cu_q_len, host_kv_len, host_cu_q_len, *,
-                   kv_layout: int = KV_TOKEN_MAJOR, stream=None) -> None:
+                   kv_layout: int = KV_TOKEN_MAJOR, stream=None, error_count=None) -> None:
     """Writes this step's K/V rows [T,Hkv,d] into the paged caches [nb,Hkv,16,d] in place."""
     hk, hc = _host_i32(host_kv_len), _host_i32(host_cu_q_len)
     a = KvAppendArgs()
@@ -268,6 +316,7 @@ def spec_kv_append(new_k, new_v, k_cache, v_cache, block_table, kv_len, cu_q_len
     a.k_cache, a.v_cache = k_cache.data_ptr(), v_cache.data_ptr()
     a.block_table, a.kv_len, a.cu_q_len = block_table.data_ptr(), kv_len.data_ptr(), cu_q_len.data_ptr()
     a.host_kv_len, a.host_cu_q_len = hk.ctypes.data, hc.ctypes.data
+    a.error_count = _dev_ptr(error_count)
     fn = lib().spec_kv_append
     fn.restype = C.c_int
     fn.argtypes = [C.c_void_p, C.c_void_p]

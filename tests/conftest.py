@@ -15,3 +15,18 @@ def pytest_configure(config):
 @pytest.fixture(scope="session")
 def golden_dir():
     return os.path.join(ROOT, "tests", "golden")
+
+
+@pytest.fixture
+def tuning(monkeypatch):
+    """Sets SPEC_VERIFY_* tuning switches for one test: the library reads its environment once,
+    so the switches are re-read after every change and once more when the test is over."""
+    from paper_2406_14066_amd import spec_verify as sv
+
+    def set_switch(name, value):
+        monkeypatch.setenv(name, str(value))
+        sv.reload_env()
+
+    yield set_switch
+    monkeypatch.undo()
+    sv.reload_env()

@@ -34,7 +34,7 @@ def oracle_reject(w):
                                 w.philox_seed, w.philox_step)
 
 
-def check_reject(w, res, ref=None, max_excluded=0):
+def check_reject(w, res, ref=None, max_excluded=0, input_errors=0):
     """Bit-exact accepted lengths and tokens for every request whose decisions are not
     near-ties.  A request is excluded from the bit-exact comparison if one of its evaluated
     accept tests has |u - p/q| < 1e-6 (the benchmark spec's category) or if the oracle's race
@@ -67,7 +67,7 @@ def check_reject(w, res, ref=None, max_excluded=0):
     assert c[0] == ref.counters[0] and c[5] == ref.counters[5]
     assert c[1] == res["accepted_len"].sum() and c[3] == c[1] + B
     assert c[2] == np.minimum(res["accepted_len"] + 1, w.q_len - 1).sum()
-    assert c[6] == 0 and c[7] == 0
+    assert c[6] == input_errors and c[7] == 0, c   # findings of the device-side input checks, abandoned requests
     if not near.any():
         np.testing.assert_array_equal(c[:4], ref.counters[:4])
     # the recorded u and p/q of every evaluated accept test

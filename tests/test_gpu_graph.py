@@ -17,12 +17,12 @@ pytestmark = pytest.mark.gpu
                                                 ("c4", dict(B=40, L_scale=0.5, V=8192), True),
                                                 ("c5", dict(L_scale=0.1, V=16384), False)],
                          ids=["c2_small", "c4_small", "c4_small_early_stop", "c5_small"])
-def test_step_replays_from_a_graph(monkeypatch, name, kw, early_stop):
+def test_step_replays_from_a_graph(tuning, name, kw, early_stop):
     import torch
     from paper_2406_14066_amd.harness import DeviceStep
     print("case graph", name, "early stop", early_stop, flush=True)
     if early_stop:   # the statistics pass in position order with placeholder records (large batches get it by themselves)
-        monkeypatch.setenv("SPEC_VERIFY_EARLY_STOP", "1")
+        tuning("SPEC_VERIFY_EARLY_STOP", 1)
     w = W.config(name, **kw)
     ds = DeviceStep(w, kv_layout=sv.KV_MFMA)
     ds.run_step()

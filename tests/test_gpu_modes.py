@@ -75,11 +75,11 @@ def test_greedy_small(harness, name, B, V, k):
 
 
 @pytest.mark.parametrize("B,V,k", [(16, 1024, 1), (7, 4100, 4), (5, 32000, 8), (3, 128256, 3)], ids=["k1", "k4", "k8", "v128256"])
-def test_greedy_with_early_stop(harness, monkeypatch, B, V, k):
+def test_greedy_with_early_stop(harness, tuning, B, V, k):
     """Greedy acceptance with the arg-max pass in position order (rows after a request's first
     mismatch are skipped); the library picks that order for large batches only, the switch forces it."""
     print("case greedy early stop", B, V, k, flush=True)
-    monkeypatch.setenv("SPEC_VERIFY_EARLY_STOP", "1")
+    tuning("SPEC_VERIFY_EARLY_STOP", 1)
     seen = set()
     for step in range(3):
         w = _logits_only("ges_k%d" % k, B, V, [k] * B, 90 + step, step)
@@ -124,11 +124,11 @@ def test_point_draft_small(harness, name, B, V, k):
 
 
 @pytest.mark.parametrize("B,V,k", [(16, 1024, 1), (7, 4100, 4), (5, 32000, 8)], ids=["k1", "k4", "k8"])
-def test_point_draft_with_early_stop(harness, monkeypatch, B, V, k):
+def test_point_draft_with_early_stop(harness, tuning, B, V, k):
     """Point-mass draft with the statistics pass in position order (rows after a request's first
     rejection are skipped); the library picks that order for large batches only, the switch forces it."""
     print("case point draft early stop", B, V, k, flush=True)
-    monkeypatch.setenv("SPEC_VERIFY_EARLY_STOP", "1")
+    tuning("SPEC_VERIFY_EARLY_STOP", 1)
     for step in range(2):
         w = _logits_only("es_k%d" % k, B, V, [k] * B, 80 + step, step)
         w.draft_tokens = _mostly_argmax_tokens(w, 13 + step, hit=0.8)

@@ -48,6 +48,34 @@ SMALL = [
     ("many_rows", dict(B=2, Hq=16, Hkv=2, d=128, kv_len=[129, 400], k=[8, 6])),   # 72 rows per KV head
 ]
 
+# more than 48 fused rows per KV head: several blocks per (request, KV head, chunk) on the matrix path
+ROW_GROUP_CASES = [
+    # name, kwargs, row tiles per block, blocks per (request, KV head, chunk)
+    ("g8_k8_k6", dict(B=2, Hq=16, Hkv=2, d=128, kv_len=[129, 400], k=[8, 6]), 3, 2),          # 72 and 56 rows
+    ("g8_k7_split", dict(B=3, Hq=16, Hkv=2, d=128, kv_len=[3000, 517, 1999], k=[7, 7, 7]), 2, 2),   # 64 rows, requests split into chunks
+    ("g16_k8", dict(B=2, Hq=16, Hkv=1, d=128, kv_len=[700, 90], k=[8, 8]), 3, 3),             # 144 rows
+    ("g16_ragged_k", dict(B=5, Hq=32, Hkv=2, d=128, kv_len=[64, 1500, 9, 333, 2048], k=[8, 0, 3, 5, 2]), 3, 3),  # requests with 1, 2 and 3 groups' worth of rows
+    ("c4_shape_k7", dict(B=20, Hq=64, Hkv=8, d=128, kv_len=[256 + 37 * i for i in range(20)], k=[7] * 20), 2, 2),
+]
+
+
+@pytest.mark.parametrize("name,kw,tiles,groups", ROW_GROUP_CASES, ids=[c[0] for c in ROW_GROUP_CASES])
+def test_many_rows_stay_on_the_matrix_path(harness, name, kw, tiles, groups):
+    print("case row groups", name, flush=True)
+    w = W.make_workload(name, V=64, dtype="bf16", draft_std=2.0, sigma=1.0, data_seed=zlib.crc32(name.encode()) % 1000,
+                        philox_seed=3, **kw)
+    ds = harness.DeviceStep(w, kv_layout=sv.KV_MFMA)
+    plan = ds.plan()
+    assert plan["attn_path"] == sv.PATH_MFMA and plan["row_tiles"] == tiles and plan["row_groups"] == groups, plan
+    ds.run_attn()
+    err = check_attn(w, ds.results()["out"])
+    # the whole step through the same path, and a second call on the same workspace
+    ds.run_step()
+    res = ds.results()
+    check_attn(w, res["out"])
+    check_reject(w, res)
+    print("%s: attn err %.2e, plan %s" % (name, err, plan))
+
 
 @pytest.mark.parametrize("layout", [sv.KV_TOKEN_MAJOR, sv.KV_MFMA], ids=["token_major", "mfma"])
 @pytest.mark.parametrize("name,kw", SMALL, ids=[s[0] for s in SMALL])
@@ -110,11 +138,11 @@ EARLY_STOP_CASES = [
 
 
 @pytest.mark.parametrize("name,kw", EARLY_STOP_CASES, ids=[c[0] for c in EARLY_STOP_CASES])
-def test_reject_sample_with_early_stop(harness, monkeypatch, name, kw):
+def test_reject_sample_with_early_stop(harness, tuning, name, kw):
     """The statistics pass in position order, skipping the rows after a request's first rejection
     (the library chooses it for large batches only; the switch forces it here)."""
     print("case early stop", name, flush=True)
-    monkeypatch.setenv("SPEC_VERIFY_EARLY_STOP", "1")
+    tuning("SPEC_VERIFY_EARLY_STOP", 1)
     B = kw["B"]
     for step in range(3):
         w = W.make_workload(name, B=B, Hq=1, Hkv=1, d=64, V=kw["V"], dtype="f32", kv_len=[16] * B, k=[kw["k"]] * B,
@@ -132,9 +160,9 @@ def test_reject_sample_with_early_stop(harness, monkeypatch, name, kw):
         check_reject(w, ds.results())
 
 
-def test_whole_step_with_early_stop(harness, monkeypatch):
+def test_whole_step_with_early_stop(harness, tuning):
     print("case early stop, fused step", flush=True)
-    monkeypatch.setenv("SPEC_VERIFY_EARLY_STOP", "1")
+    tuning("SPEC_VERIFY_EARLY_STOP", 1)
     w = W.config("c4", B=24, L_scale=0.5)
     ds, res = _run(harness, w, sv.KV_MFMA)
     check_attn(w, res["out"])

@@ -243,3 +243,128 @@ def test_static_scratch_entry_refuses_what_does_not_fit():
     bad.q = None
     assert L.spec_verify_step_static(C.byref(bad), C.byref(_reject()), None) == sv.SPEC_EINVAL
     assert L.spec_verify_step_static(C.byref(_attn()), C.byref(_reject(B=2, q_len=(2, 2))), None) == sv.SPEC_EINVAL
+
+
+# --------------------------------------------------------------------------
+# length buckets, host copies checked on request, plan query, tuning switches
+# --------------------------------------------------------------------------
+def test_validate_flag_checks_the_host_copies():
+    a = _attn(kv_len=(40, 20), max_blocks=4)
+    table = np.array([[0, 1, 2, 9], [3, 4, 9, 9]], dtype=np.int32)       # entries past the pages in use are not looked at
+    a.host_block_table = table.ctypes.data
+    a.validate = 1
+    assert sv.spec_validate_attn(a) == sv.SPEC_OK
+    table[0, 2] = 16                                                        # num_blocks is 16: out of range
+    assert sv.spec_validate_attn(a) == sv.SPEC_EINVAL
+    assert sv.lib().spec_verify_attn(C.byref(a), FAKE, 1 << 30, None) == sv.SPEC_EINVAL
+    table[0, 2] = -1
+    assert sv.spec_validate_attn(a) == sv.SPEC_EINVAL
+    a.validate = 0                                                          # not asked for: not looked at
+    assert sv.spec_validate_attn(a) == sv.SPEC_OK
+    a.validate = 2
+    assert sv.spec_validate_attn(a) == sv.SPEC_EINVAL
+
+    r = _reject(V=32, q_len=(3, 2))
+    tok = np.array([1, 31, 0], dtype=np.int32)
+    r.host_draft_tokens = tok.ctypes.data
+    r.validate = 1
+    assert sv.spec_validate_reject(r) == sv.SPEC_OK
+    tok[1] = 32
+    assert sv.spec_validate_reject(r) == sv.SPEC_EINVAL
+    assert sv.lib().spec_reject_sample(C.byref(r), FAKE, 1 << 30, None) == sv.SPEC_EINVAL
+    tok[1] = -3
+    assert sv.spec_validate_reject(r) == sv.SPEC_EINVAL
+    r.philox_step_device = FAKE + 4                                         # must be 8-byte aligned
+    r.validate = 0
+    assert sv.spec_validate_reject(r) == sv.SPEC_EINVAL
+
+
+def test_length_bucket_arguments():
+    a = _attn(kv_len=(40, 20), max_blocks=4)
+    a.max_kv_len = 64
+    assert sv.spec_validate_attn(a) == sv.SPEC_OK
+    a.max_kv_len = 65                      # 5 pages do not fit a block-table row of 4
+    assert sv.spec_validate_attn(a) == sv.SPEC_EINVAL
+    a.max_kv_len = 32                      # a host length above the bucket
+    assert sv.spec_validate_attn(a) == sv.SPEC_EINVAL
+    a.max_kv_len = -1
+    assert sv.spec_validate_attn(a) == sv.SPEC_EINVAL
+    a.max_kv_len = 64
+    a.host_kv_len = None                   # with a bucket the host lengths are optional
+    assert sv.spec_validate_attn(a) == sv.SPEC_OK
+    a.max_kv_len = 0
+    assert sv.spec_validate_attn(a) == sv.SPEC_EINVAL
+
+
+def test_bucket_plan_does_not_depend_on_the_lengths():
+    """Under a length bucket the split, the grid and the workspace depend on the bound only, so a
+    launch captured for one set of lengths stays valid for another."""
+    q_len = (3,) * 6
+    plans = []
+    for lens in [(100,) * 6, (5, 900, 64, 65, 1000, 3), None]:
+        a = _attn(B=6, Hq=8, Hkv=2, kv_len=lens or (1,) * 6, q_len=q_len, max_blocks=64)
+        a.max_kv_len = 1024
+        if lens is None:
+            a.host_kv_len = None
+        r = _reject(B=6, V=4096, q_len=q_len)
+        plans.append(sv.spec_verify_plan(a, r))
+    assert plans[0] == plans[1] == plans[2]
+    assert plans[0]["attn_path"] == sv.PATH_MFMA
+    assert plans[0]["chunk_tokens"] * plans[0]["max_chunks"] >= 1024
+    # without a bucket the plan follows the host lengths
+    a = _attn(B=6, Hq=8, Hkv=2, kv_len=(100,) * 6, q_len=q_len, max_blocks=64)
+    exact = sv.spec_verify_plan(a, _reject(B=6, V=4096, q_len=q_len))
+    assert exact["chunk_tokens"] * exact["max_chunks"] < 1024
+
+
+@pytest.mark.parametrize("Hq,Hkv,k,path,tiles,groups", [
+    (32, 32, 8, sv.PATH_MFMA, 1, 1),     # 9 rows per KV head
+    (64, 8, 2, sv.PATH_MFMA, 2, 1),      # 24 rows
+    (32, 8, 8, sv.PATH_MFMA, 3, 1),      # 36 rows
+    (64, 8, 5, sv.PATH_MFMA, 3, 1),      # 48 rows
+    (64, 8, 6, sv.PATH_MFMA, 2, 2),      # 56 rows: two blocks of two tiles
+    (64, 8, 7, sv.PATH_MFMA, 2, 2),      # 64 rows
+    (64, 8, 8, sv.PATH_MFMA, 3, 2),      # 72 rows
+    (16, 1, 8, sv.PATH_MFMA, 3, 3),      # 144 rows: the widest group at the longest draft
+    (16, 1, 3, sv.PATH_MFMA, 2, 2),      # 64 rows
+])
+def test_every_supported_row_count_takes_the_matrix_path(Hq, Hkv, k, path, tiles, groups):
+    B = 4
+    a = _attn(B=B, Hq=Hq, Hkv=Hkv, kv_len=(300,) * B, q_len=(k + 1,) * B, max_blocks=32)
+    info = sv.spec_verify_plan(a, None)
+    assert (info["attn_path"], info["row_tiles"], info["row_groups"]) == (path, tiles, groups), info
+    assert info["launches"] == 1
+    # the other page layout, fp32 and d = 64 take the generic kernels
+    assert sv.spec_verify_plan(_attn(B=B, Hq=Hq, Hkv=Hkv, kv_len=(300,) * B, q_len=(k + 1,) * B, max_blocks=32,
+                                     layout=sv.KV_TOKEN_MAJOR), None)["attn_path"] == sv.PATH_GENERIC
+    assert sv.spec_verify_plan(_attn(B=B, Hq=Hq, Hkv=Hkv, d=64, kv_len=(300,) * B, q_len=(k + 1,) * B,
+                                     max_blocks=32), None)["attn_path"] == sv.PATH_GENERIC
+
+
+def test_tuning_switches_are_read_once_and_on_reload(monkeypatch):
+    a = _attn(B=4, Hq=8, Hkv=2, kv_len=(300,) * 4, q_len=(3,) * 4, max_blocks=32)
+    assert sv.spec_verify_plan(a, None)["attn_path"] == sv.PATH_MFMA
+    monkeypatch.setenv("SPEC_VERIFY_FORCE_GENERIC", "1")
+    assert sv.spec_verify_plan(a, None)["attn_path"] == sv.PATH_MFMA        # not re-read on the call path
+    sv.reload_env()
+    try:
+        assert sv.spec_verify_plan(a, None)["attn_path"] == sv.PATH_GENERIC
+    finally:
+        monkeypatch.undo()
+        sv.reload_env()
+    assert sv.spec_verify_plan(a, None)["attn_path"] == sv.PATH_MFMA
+
+
+def test_plan_is_reused_for_an_unchanged_shape_and_follows_a_changed_one():
+    q_len = (3,) * 6
+    a = _attn(B=6, Hq=8, Hkv=2, kv_len=(100, 200, 300, 400, 500, 600), q_len=q_len, max_blocks=64)
+    r = _reject(B=6, V=4096, q_len=q_len)
+    first = sv.spec_verify_plan(a, r)
+    assert sv.spec_verify_plan(a, r) == first
+    hk = np.array([100, 200, 300, 400, 500, 1000], dtype=np.int32)        # same buffer shape, one longer request
+    a.host_kv_len = hk.ctypes.data
+    longer = sv.spec_verify_plan(a, r)
+    assert longer["chunk_tokens"] * longer["max_chunks"] >= 1000 > first["chunk_tokens"] * first["max_chunks"]
+    bad = np.array([100, 200, 300, 400, 500, 2], dtype=np.int32)          # kv_len < q_len: the cached plan must not hide it
+    a.host_kv_len = bad.ctypes.data
+    assert sv.lib().spec_verify_step(C.byref(a), C.byref(r), FAKE, 1 << 30, None) == sv.SPEC_EINVAL

@@ -17,8 +17,9 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 @pytest.mark.skipif(shutil.which(HIPCC) is None and not os.path.exists(HIPCC), reason="hipcc not installed")
 def test_step_kernel_uses_no_private_memory_and_keeps_its_occupancy(tmp_path):
     flags = [f for f in B.HIPCC_FLAGS if f not in ("-shared", "-fPIC")]
+    asm = tmp_path / "step.s"
     cmd = [HIPCC] + flags + ["-I", os.path.join(B.ROOT, "include"), "-I", B.CSRC, "-Rpass-analysis=kernel-resource-usage",
-                             "-c", "-o", str(tmp_path / "step.o"), os.path.join(B.CSRC, "step_kernel.hip")]
+                             "-S", "--cuda-device-only", "-o", str(asm), os.path.join(B.CSRC, "step_kernel.hip")]
     out = subprocess.run(cmd, check=True, capture_output=True, text=True).stderr
     kernels = {}
     name = None
@@ -32,11 +33,28 @@ def test_step_kernel_uses_no_private_memory_and_keeps_its_occupancy(tmp_path):
         if m and name is not None:
             kernels[name][m.group(1).split(" ")[0]] = int(m.group(2))
     assert len(kernels) == 14, sorted(kernels)
-    for (nt, has_attn, has_reject, split_p), r in kernels.items():
+    # instructions that touch private memory, per kernel, from the assembly
+    touches = {}
+    name = None
+    for line in open(asm):
+        m = re.match(r"^(\S*spec_step_kernelILi(\d)ELb(\d)ELb(\d)ELb(\d)E\S*):\s", line)
+        if m:
+            name = tuple(int(x) for x in m.groups()[1:])
+            touches[name] = 0
+        elif name is not None and re.search(r"^\s+scratch_(load|store)", line):
+            touches[name] += 1
+        elif "-- End function" in line:
+            name = None
+    assert set(touches) == set(kernels)
+    for key, r in kernels.items():
+        nt, has_attn, has_reject, split_p = key
+        # an argument struct or an unrolled array that fell back to private memory takes hundreds of
+        # bytes; a few dead spill slots of scalar registers (no instruction touches them) are harmless
+        assert r["ScratchSize"] <= 64, (key, r)
         if nt <= 2:
-            assert r["ScratchSize"] == 0, ((nt, has_attn, has_reject, split_p), r)
+            assert touches[key] == 0, (key, r, touches[key])
         else:
-            assert r["ScratchSize"] <= 64, ((nt, has_attn, has_reject, split_p), r)   # three row tiles: a few spilled registers
+            assert touches[key] <= 8, (key, r, touches[key])   # three row tiles: a few spilled registers
         if not has_attn:
             assert r["Occupancy"] >= 4, r       # rejection-only launch
         elif nt == 1:
