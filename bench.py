@@ -3,8 +3,11 @@
 
 A "step" is one pass of the whole hot path -- lookahead attention over the paged KV
 cache, then rejection sampling with bonus token -- over one batch of seeded synthetic
-input that is already resident in HBM.  The default workload is the Llama-2-7B-shaped
-single-layer verify (B=8, L=2048, k=4, 32/32 heads, d=128, bf16 paged KV, V=32000).
+input that is already resident in HBM.  The headline workload is the largest of the
+named configurations that fits one GPU: c4, the 70B-shaped GQA batch (B=256, L uniform
+in [256,1024], k=2, 64/8 heads, d=128, bf16 paged KV, V=32000).  The other named
+workloads (c2, a c3 sweep point, c5) and a c4-shaped batch at k=7 (more than 48 fused
+query rows per KV head) are timed in the same run and reported under "workloads".
 
 KV pools and logits are rotated over several device copies so that consecutive steps
 do not find their inputs in the 256 MB last-level cache.
@@ -36,12 +39,17 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5"])
+    ap.add_argument("--workload", default="c4", choices=["c2", "c3", "c4", "c5", "c4_k7"],
+                    help="the workload of the headline figures")
     ap.add_argument("--k", type=int, default=None, help="speculation length of the c3 sweep point")
     ap.add_argument("--alpha", type=float, default=None, help="acceptance level of the c3 sweep point")
     ap.add_argument("--rotate", type=int, default=0, help="device copies of KV/logits to cycle through (0 = auto)")
     ap.add_argument("--accept-mode", default="sample", choices=["sample", "greedy", "point"],
                     help="acceptance rule: the stochastic rule (headline), greedy, or stochastic against a point-mass draft")
+    ap.add_argument("--setup-steps", type=int, default=300,
+                    help="untimed steps before the W warm-up steps: the device needs some tens of milliseconds of "
+                         "load to reach its sustained clocks (the first hundred steps of c4 run 2-3%% slower)")
+    ap.add_argument("--only", action="store_true", help="time the headline workload only (no \"workloads\" entries)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the same steps")
     ap.add_argument("--events-in-value-region", action="store_true",
@@ -51,7 +59,7 @@ def parse():
 
 
 def traffic_from_profile(workload):
-    """HBM bytes per attention launch measured with rocprofv3 counters, if a summary is committed."""
+    """HBM bytes per launch measured with rocprofv3 counters, if a summary is committed."""
     path = os.path.join(ROOT, "profiles", "spec_step_kernel_%s_pmc.txt" % workload)
     try:
         for line in open(path):
@@ -62,30 +70,30 @@ def traffic_from_profile(workload):
     return None
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (the step has no multi-GPU path); use --gpus 1",
-              file=sys.stderr)
-        sys.exit(2)
-
-    import torch
+def make_workload(name, k=None, alpha=None):
     from paper_2406_14066_amd import workloads as W
+    if name == "c3":
+        return W.config("c3", k=k, alpha=alpha)
+    if name == "c4_k7":
+        w = W.config("c4", k=7)
+        w.name = "c4_k7"
+        return w
+    return W.config(name)
+
+
+def describe(w):
+    return ("%s: B=%d, L=%s, k=%s, Hq/Hkv=%d/%d, d=%d, bf16 paged KV (block 16, shuffled table), V=%d fp32 logits"
+            % (w.name, w.B, _span(w.kv_len), _span(w.k), w.Hq, w.Hkv, w.d, w.V))
+
+
+def measure(w, args, mode, with_graph):
+    """Times K steps of workload w: wall clock without events, kernel time with events attached."""
+    import torch
     from paper_2406_14066_amd import spec_verify as sv
     from paper_2406_14066_amd.harness import DeviceStep
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(2)
-    sv.lib()  # fail loudly if the HIP library is missing
-
-    kw = {}
-    if args.workload == "c3":
-        kw = dict(k=args.k, alpha=args.alpha)
-    w = W.config(args.workload, **kw)
-    mode = {"sample": sv.ACCEPT_SAMPLE, "greedy": sv.ACCEPT_GREEDY, "point": sv.ACCEPT_POINT_DRAFT}[args.accept_mode]
     ds = DeviceStep(w, kv_layout=sv.KV_MFMA, with_debug=False, accept_mode=mode)
-
+    plan = ds.plan()
     attn_bytes = w.attn_algorithmic_bytes()
     # without a draft distribution only the target rows are read
     rej_bytes = w.reject_algorithmic_bytes() if mode == sv.ACCEPT_SAMPLE else w.T * w.V * 4
@@ -95,17 +103,16 @@ def main():
     # last-level cache still served a few per cent of the (non-temporal) reads
     nrot = args.rotate or max(4, int(np.ceil(4.0e9 / max(kv_bytes + rej_bytes, 1))))
     nrot = min(nrot, 16)
-
-    # rotated copies: same bytes at different addresses
-    variants = [(a, r, None) for a, r in ds.rotated(nrot)]
-
+    variants = ds.rotated(nrot)   # same bytes at different addresses
     stream = torch.cuda.current_stream()
 
     def run(n, first=0):
         for i in range(n):
-            a, r, _ = variants[(first + i) % nrot]
+            a, r = variants[(first + i) % nrot]
             sv.spec_verify_step(a, r, ds.workspace, stream)
 
+    run(args.setup_steps)
+    torch.cuda.synchronize()
     run(args.warmup)
     torch.cuda.synchronize()
 
@@ -116,17 +123,18 @@ def main():
     # serving loop would not pay.  --events-in-value-region folds the two into one.
     events_in_region = args.events_in_value_region
     if events_in_region:
-        sv.spec_profile_begin(args.steps)
+        sv.spec_profile_begin(args.steps * 2)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     run(args.steps, first=args.warmup)
+    t_enqueued = time.perf_counter()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     if events_in_region:
         kt = sv.spec_profile_end()
         sec_per_step_events = (t1 - t0) / args.steps
     else:
-        sv.spec_profile_begin(args.steps)
+        sv.spec_profile_begin(args.steps * 2)
         torch.cuda.synchronize()
         t2 = time.perf_counter()
         run(args.steps, first=args.warmup)
@@ -134,20 +142,17 @@ def main():
         t3 = time.perf_counter()
         kt = sv.spec_profile_end()
         sec_per_step_events = (t3 - t2) / args.steps
-
     sec_per_step = (t1 - t0) / args.steps
-    value = w.verified_tokens() / sec_per_step
 
     # The same steps replayed from one captured HIP graph (one step per rotated copy): what is
     # left of the launch gaps when the host is out of the loop.  Reported beside the eager figure.
     graph_info = None
-    if not args.no_graph:
+    if with_graph:
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=side):
-            for i in range(nrot):
-                a, r, _ = variants[i]
+            for a, r in variants:
                 sv.spec_verify_step(a, r, ds.workspace, torch.cuda.current_stream())
         torch.cuda.synchronize()
         replays = max(args.steps // nrot, 1)
@@ -163,8 +168,10 @@ def main():
         graph_info = {"ms_per_step": graph_sec * 1e3, "value": w.verified_tokens() / graph_sec,
                       "steps": replays * nrot, "steps_per_graph": nrot,
                       "achieved_GBps": step_bytes / graph_sec / 1e9}
+        del graph
     res = ds.results()
-    emitted_per_step = int(res["counters"][3]) // max(int(res["counters"][5]) // w.B, 1)
+    calls = max(int(res["counters"][5]) // w.B, 1)
+    emitted_per_step = int(res["counters"][3]) // calls
     # logit bytes of the rows up to each request's first rejection: what the step needs at least
     # (the library reads no more than these when it takes the statistics pass in position order,
     # which it does for large batches with one draft length)
@@ -174,13 +181,81 @@ def main():
     rej_bytes_needed = int(rows_needed.sum()) * w.V * 4
 
     kernel_us = {k: (1e3 * ms / n if n else None) for k, (ms, n) in kt.items()}
-    step_us = kernel_us["step"]
+    # the step is the one launch of the step kernel (plus a merge launch only when a request has more than 64 chunks)
+    step_us = kernel_us["step"] + (kernel_us["attn_combine"] or 0.0)
     achieved = step_bytes / (step_us * 1e-6) / 1e9
+    out = dict(
+        w=w, ds=ds, res=res, plan=plan, nrot=nrot, sec_per_step=sec_per_step, sec_per_step_events=sec_per_step_events,
+        host_us_per_call=(t_enqueued - t0) / args.steps * 1e6, kernel_us=kernel_us, step_us=step_us, achieved=achieved,
+        attn_bytes=attn_bytes, rej_bytes=rej_bytes, step_bytes=step_bytes, rej_bytes_needed=rej_bytes_needed,
+        emitted_per_step=emitted_per_step, graph_info=graph_info, events_in_region=events_in_region,
+        near_tie_accept_tests_per_step=int(res["counters"][4]) // calls,
+        input_errors=int(res["counters"][6]), abandoned=int(res["counters"][7]),
+    )
+    return out
+
+
+def brief(mm, traffic):
+    """One entry of "workloads"."""
+    w = mm["w"]
+    return {
+        "workload": describe(w),
+        "verified_tokens_per_step": w.verified_tokens(),
+        "value": w.verified_tokens() / mm["sec_per_step"],
+        "ms_per_step": mm["sec_per_step"] * 1e3,
+        "kernel_us": mm["step_us"],
+        "algorithmic_bytes": mm["step_bytes"],
+        "achieved_GBps": mm["achieved"],
+        "frac": mm["achieved"] / HBM_PEAK_GBS,
+        "traffic": traffic,
+        "attention_path": {1: "matrix instructions", 2: "generic"}[mm["plan"]["attn_path"]],
+        "row_tiles": mm["plan"]["row_tiles"], "row_groups": mm["plan"]["row_groups"],
+        "chunk_tokens": mm["plan"]["chunk_tokens"], "launches": mm["plan"]["launches"],
+        "early_stop": mm["plan"]["early_stop"],
+        "emitted_tokens_per_step": mm["emitted_per_step"],
+        "near_tie_accept_tests_per_step": mm["near_tie_accept_tests_per_step"],
+        "rotated_copies": mm["nrot"],
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the step has no multi-GPU path); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2406_14066_amd import spec_verify as sv
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    sv.lib()  # fail loudly if the HIP library is missing
+
+    mode = {"sample": sv.ACCEPT_SAMPLE, "greedy": sv.ACCEPT_GREEDY, "point": sv.ACCEPT_POINT_DRAFT}[args.accept_mode]
+
+    # the other workloads first (each frees its device memory before the next), the headline one last
+    others = {}
+    if not args.only:
+        for name, kw in [("c2", {}), ("c3", dict(k=4, alpha=0.7)), ("c5", {}), ("c4_k7", {})]:
+            if name == args.workload:
+                continue
+            wo = make_workload(name, **kw)
+            mo = measure(wo, args, mode, with_graph=False)
+            others[name] = brief(mo, traffic_from_profile(name) if mode == sv.ACCEPT_SAMPLE else None)
+            del mo, wo
+            torch.cuda.empty_cache()
+
+    w = make_workload(args.workload, args.k, args.alpha)
+    mm = measure(w, args, mode, with_graph=not args.no_graph)
+    res = mm["res"]
+    sec_per_step = mm["sec_per_step"]
     traffic = traffic_from_profile(args.workload) if mode == sv.ACCEPT_SAMPLE else None
 
     out = {
         "metric": "verified tokens/s per MI355X for spec-verify step",
-        "value": value,
+        "value": w.verified_tokens() / sec_per_step,
         "unit": "tokens/s",
         "n_gpus": 1,
         "steps": args.steps,
@@ -192,57 +267,68 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {
-            "workload": "%s: B=%d, L=%s, k=%s, Hq/Hkv=%d/%d, d=%d, bf16 paged KV (block 16, shuffled table), V=%d fp32 logits"
-                        % (w.name, w.B, _span(w.kv_len), _span(w.k), w.Hq, w.Hkv, w.d, w.V),
+            "workload": describe(w),
             "kv_layout": "mfma-tiled pages",
             "accept_mode": args.accept_mode,
-            "rotated_copies": nrot,
+            "rotated_copies": mm["nrot"],
+            "untimed_setup_steps_before_warmup": args.setup_steps,
             "verified_tokens_per_step": w.verified_tokens(),
-            "emitted_tokens_per_step": emitted_per_step,
-            "goodput_tokens_per_s": emitted_per_step / sec_per_step,
+            "emitted_tokens_per_step": mm["emitted_per_step"],
+            "goodput_tokens_per_s": mm["emitted_per_step"] / sec_per_step,
+            "plan": {k: v for k, v in mm["plan"].items()},
         },
         "step_hbm": {
-            "algorithmic_bytes": step_bytes,
-            "achieved_GBps": step_bytes / sec_per_step / 1e9,
-            "frac_of_peak": step_bytes / sec_per_step / 1e9 / HBM_PEAK_GBS,
+            "algorithmic_bytes": mm["step_bytes"],
+            "achieved_GBps": mm["step_bytes"] / sec_per_step / 1e9,
+            "frac_of_peak": mm["step_bytes"] / sec_per_step / 1e9 / HBM_PEAK_GBS,
         },
-        "kernel_us": kernel_us,
-        "graph_replay": graph_info,
+        "kernel_us": mm["kernel_us"],
+        "host_us_per_call": mm["host_us_per_call"],
+        "graph_replay": mm["graph_info"],
+        "decisions": {
+            # counters[4]: evaluated accept tests within 1e-6 of their uniform, per step (counted by the kernel)
+            "near_tie_accept_tests_per_step": mm["near_tie_accept_tests_per_step"],
+            "device_side_input_errors": mm["input_errors"],
+            "abandoned_requests": mm["abandoned"],
+        },
         "roofline": {
             "kernel": "spec_step_kernel (whole step in one launch: attention over the paged KV cache + rejection sampling)",
             "bound": "hbm",
-            "achieved": achieved,
+            "achieved": mm["achieved"],
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
-            "frac": achieved / HBM_PEAK_GBS,
+            "frac": mm["achieved"] / HBM_PEAK_GBS,
             "traffic": traffic,
-            "algorithmic_bytes_per_launch": step_bytes,
-            "attention_bytes": attn_bytes,
-            "rejection_bytes": rej_bytes,
-            "rejection_bytes_up_to_first_rejection": rej_bytes_needed,
+            "algorithmic_bytes_per_launch": mm["step_bytes"],
+            "attention_bytes": mm["attn_bytes"],
+            "rejection_bytes": mm["rej_bytes"],
+            "rejection_bytes_up_to_first_rejection": mm["rej_bytes_needed"],
             "events_in_timed_region": True,
-            "kernel_time_region": ("the K steps that give value" if events_in_region else
+            "kernel_time_region": ("the K steps that give value" if mm["events_in_region"] else
                                    "a second timed region of K steps with an event pair attached to every launch"),
-            "ms_per_step_with_events": sec_per_step_events * 1e3,
+            "ms_per_step_with_events": mm["sec_per_step_events"] * 1e3,
         },
+        "workloads": others,
     }
 
     if not args.no_cpu_baseline:
         import oracle
-        # the oracle as it stands, single thread, on whole steps of this workload until about
-        # ten seconds have passed (at least one step)
+        # The oracle as it stands, single thread, on whole steps of the headline workload until about
+        # ten seconds have passed (at least one step).  Its decisions are compared with the GPU's here,
+        # and the decisions the oracle marks as near ties are counted.
         reps, t_attn, t_rej = 0, 0.0, 0.0
+        ref = None
         while reps == 0 or (t_attn + t_rej < 10.0 and reps < 1000):
             t2 = time.perf_counter()
             oracle.verify_attn(w.q, w.k_pages, w.v_pages, w.block_table, w.kv_len, w.cu_q_len)
             t3 = time.perf_counter()
             if mode == sv.ACCEPT_SAMPLE:
-                oracle.reject_sample(w.target_logits, w.draft_logits, w.draft_tokens, w.cu_q_len, w.philox_seed,
-                                     w.philox_step)
+                ref = oracle.reject_sample(w.target_logits, w.draft_logits, w.draft_tokens, w.cu_q_len, w.philox_seed,
+                                           w.philox_step)
             elif mode == sv.ACCEPT_GREEDY:
-                oracle.reject_greedy(w.target_logits, w.draft_tokens, w.cu_q_len)
+                ref = oracle.reject_greedy(w.target_logits, w.draft_tokens, w.cu_q_len)
             else:
-                oracle.reject_onehot(w.target_logits, w.draft_tokens, w.cu_q_len, w.philox_seed, w.philox_step)
+                ref = oracle.reject_onehot(w.target_logits, w.draft_tokens, w.cu_q_len, w.philox_seed, w.philox_step)
             t4 = time.perf_counter()
             t_attn += t3 - t2
             t_rej += t4 - t3
@@ -255,6 +341,18 @@ def main():
             "sample": "the whole %s step %d times (attention %.2f s + rejection sampling %.2f s per step), single thread; host has %d cpus"
                       % (w.name, reps, t_attn / reps, t_rej / reps, os.cpu_count()),
         }
+        near_accept = 0
+        if ref.dec_u.size:
+            with np.errstate(invalid="ignore"):
+                near_accept = int((np.abs(ref.dec_u - ref.dec_ratio) < 1e-6).sum())
+        near_race = int((ref.race_margin < 1e-5).sum())
+        out["decisions"].update({
+            "oracle_near_tie_accept_tests": near_accept,
+            "oracle_near_tie_races": near_race,
+            "requests_excluded_from_exact_comparison": near_accept + near_race,
+            "accepted_len_equal_to_oracle": bool((res["accepted_len"] == ref.accepted_len).all()),
+            "next_token_equal_to_oracle": bool((res["next_token"] == ref.next_token).all()),
+        })
     print(json.dumps(out))
 
 

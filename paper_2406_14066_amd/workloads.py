@@ -209,7 +209,7 @@ def config(name: str, *, k: Optional[int] = None, alpha: Optional[float] = None,
            with_kv: bool = True, with_logits: bool = True) -> VerifyWorkload:
     """The five named workloads ("c1".."c5").  ``B``, ``L_scale`` and ``V`` shrink a
     workload for tests that need the CPU oracle to finish quickly; ``k`` and ``alpha``
-    select the point of the c3 sweep."""
+    select the point of the c3 sweep (``k`` also overrides c4's draft length of 2)."""
     name = name.lower()
     if name == "c1":
         # tiny fp32: one request, 128 tokens as 8 consecutive pages with the identity table
@@ -238,7 +238,7 @@ def config(name: str, *, k: Optional[int] = None, alpha: Optional[float] = None,
         rng = np.random.default_rng(40)
         lens = rng.integers(int(256 * L_scale), int(1024 * L_scale) + 1, size=b)
         return make_workload("c4", B=b, Hq=64, Hkv=8, d=128, V=V or 32000, dtype="bf16",
-                             kv_len=np.maximum(lens, 3), k=[2] * b, draft_std=3.0,
+                             kv_len=np.maximum(lens, 9), k=[2 if k is None else k] * b, draft_std=3.0,
                              sigma=_sigma(32000, 3.0, 0.6), data_seed=4, philox_seed=4,
                              with_kv=with_kv, with_logits=with_logits)
     if name == "c5":
