@@ -248,10 +248,11 @@ spec_status spec_verify_step_static(const spec_attn_args *attn, const spec_rejec
 #define SPEC_PATH_GENERIC 2  /* scalar attention kernel + merge kernel (fp32, token-major pages, d = 64) */
 typedef struct {
     int32_t attn_path;       /* SPEC_PATH_* */
-    int32_t row_tiles;       /* 16-row tiles of query rows per attention block (matrix path) */
-    int32_t row_groups;      /* attention blocks that share the page stream of one (request, KV head, chunk):
-                                more than 48 fused rows per KV head are spread over several blocks placed
-                                on the same XCD, so that the second reader finds the pages in its L2 */
+    int32_t row_tiles;       /* 16-row tiles of query rows per wavefront (matrix path, 1..3) */
+    int32_t row_groups;      /* groups of wavefronts inside an attention block (1, 2 or 4): with more than
+                                48 fused rows per KV head the block's wavefronts split the rows instead of
+                                the pages and read every page side by side, so K and V still cross the
+                                memory interface once */
     int32_t chunk_tokens;    /* bound of the tokens per chunk of the split over the KV length */
     int32_t max_chunks;      /* chunks of the longest request the plan allows for */
     int32_t launches;        /* kernel launches of the step */

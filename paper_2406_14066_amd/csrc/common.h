@@ -32,8 +32,8 @@ struct AttnPlan {
     int32_t max_chunks;
     int32_t max_q_len;
     int32_t use_mfma;      // 1: bf16 matrix-instruction kernel, 0: generic kernel
-    int32_t row_tiles;     // 16-row tiles of query rows per attention block (mfma kernel, 1..3)
-    int32_t row_groups;    // blocks that share one (request, KV head, chunk): row_groups * row_tiles tiles cover max_q_len * (Hq/Hkv) rows
+    int32_t row_tiles;     // 16-row tiles of query rows per wave group (mfma kernel, 1..3)
+    int32_t row_groups;    // wave groups per attention block (1, 2 or 4): row_groups * row_tiles tiles cover max_q_len * (Hq/Hkv) rows
     int32_t capacity_tokens;  // longest kv_len the plan allows for (chunk_tokens * max_chunks, capped by the bucket)
     int32_t fused_combine; // mfma kernel merges the chunk partials itself (few chunks) or leaves it to the combine kernel
     size_t acc_bytes;
@@ -65,7 +65,7 @@ struct AttnParams {
     float *out;
     float *ws_acc;
     float *ws_ml;
-    unsigned long long *tickets;  // [B * Hkv * row_groups]
+    unsigned long long *tickets;  // [B * Hkv]
     unsigned long long *errors;   // findings of the device-side input checks are added here (may be null)
 };
 static_assert(sizeof(AttnParams) == 22 * 4 + 11 * 8, "AttnParams has padding");
@@ -137,8 +137,8 @@ struct LaunchEvents {
 };
 
 // One launch for the whole step (either half may be absent).  `attn` needs the
-// matrix-instruction path (bf16, SPEC_KV_MFMA, d = 128, row_tiles <= 3; ap.row_groups blocks per
-// (request, KV head, chunk)).  `order` may be null.
+// matrix-instruction path (bf16, SPEC_KV_MFMA, d = 128; row_tiles tiles per wave group, ap.row_groups
+// wave groups per block).  `order` may be null.
 int step_attn_items(const AttnParams &ap);   // attention blocks of the launch
 hipError_t launch_step_fused(const AttnParams *attn, int row_tiles, const RejectParams *reject, const UnitOrder *order,
                              LaunchEvents events, hipStream_t stream);

@@ -298,8 +298,8 @@ spec_status validate_reject(const spec_reject_args *r)
 // ---------------------------------------------------------------------------
 // Planning.
 // ---------------------------------------------------------------------------
-// Split of the KV length.  The matrix-instruction kernel runs row_groups blocks per (request,
-// KV head, chunk); the chunk is sized so that the launch has about one block per compute unit
+// Split of the KV length.  The matrix-instruction kernel runs one block per (request, KV head,
+// chunk); the chunk is sized so that the launch has about one block per compute unit
 // (two with three row tiles), in multiples of the 16 tokens of a page.  The longest length the
 // plan allows for is the caller's bucket (max_kv_len) or, without one, the longest host length.
 AttnPlan plan_attn(const spec_attn_args *a, const Tuning &tu)
@@ -319,11 +319,13 @@ AttnPlan plan_attn(const spec_attn_args *a, const Tuning &tu)
     pl.row_groups = 1;
     pl.row_tiles = tiles;
     if (pl.use_mfma) {
-        // A block holds up to three 16-row tiles of query rows in registers.  More rows per KV
-        // head (long drafts with wide query groups) are spread evenly over several blocks that
-        // walk the same pages side by side on one XCD.
-        pl.row_groups = (tiles + 2) / 3;
+        // A wavefront holds up to three 16-row tiles of query rows in registers.  With up to 48 rows
+        // per KV head the block's four wavefronts share the pages between them; with more (long
+        // drafts on wide query groups) they form 2 or 4 groups that each own a share of the rows and
+        // walk all pages, reading them side by side.
+        pl.row_groups = tiles <= 3 ? 1 : (tiles <= 6 ? 2 : 4);
         pl.row_tiles = (tiles + pl.row_groups - 1) / pl.row_groups;
+        if (pl.row_groups > 1 && pl.row_tiles < 2) pl.row_tiles = 2;
         // Splitting costs (partials, a merge, more block start-ups), so the longest request is split
         // only as far as needed to give every compute unit a block.  With three row tiles the
         // wavefronts spend a larger share of their time on arithmetic and need a second block beside
@@ -333,14 +335,17 @@ AttnPlan plan_attn(const spec_attn_args *a, const Tuning &tu)
         const long cus = compute_units();
         long target_blocks = pl.row_tiles >= 3 ? 2 * cus - cus / 8 : cus;
         if (tu.target_blocks > 0) target_blocks = tu.target_blocks;
-        const int64_t units = (int64_t)a->B * a->Hkv * pl.row_groups;
+        const int64_t units = (int64_t)a->B * a->Hkv;
         int64_t nsplit = (target_blocks + units - 1) / units;
         if (nsplit < 1) nsplit = 1;
         int64_t chunk = (max_len + nsplit - 1) / nsplit;
         chunk = (chunk + SPEC_BLOCK_SIZE - 1) / SPEC_BLOCK_SIZE * SPEC_BLOCK_SIZE;
         if (chunk < 64) chunk = 64;
-        if (chunk > 4096) chunk = 4096;  // a wavefront holds its pages' block-table entries one per lane
-        if (tu.chunk > 0) chunk = tu.chunk;
+        // a wavefront holds its pages' block-table entries one per lane, and takes every
+        // (4 / row_groups)-th page of the chunk
+        const int64_t chunk_cap = 4096 / pl.row_groups;
+        if (chunk > chunk_cap) chunk = chunk_cap;
+        if (tu.chunk > 0 && tu.chunk <= chunk_cap) chunk = tu.chunk;
         pl.chunk_tokens = (int32_t)chunk;
     } else {
         pl.chunk_tokens = 256;  // one key per thread of the generic kernel
@@ -353,7 +358,7 @@ AttnPlan plan_attn(const spec_attn_args *a, const Tuning &tu)
     const size_t slots = (pl.use_mfma && pl.max_chunks == 1) ? 0 : (size_t)a->T * a->Hq * pl.max_chunks;
     pl.acc_bytes = align_up(slots * a->d * sizeof(float));
     pl.ml_bytes = align_up(slots * 2 * sizeof(float));
-    pl.ticket_bytes = align_up((size_t)a->B * a->Hkv * pl.row_groups * sizeof(unsigned long long));
+    pl.ticket_bytes = align_up((size_t)a->B * a->Hkv * sizeof(unsigned long long));
     pl.total_bytes = pl.acc_bytes + pl.ml_bytes + pl.ticket_bytes;
     return pl;
 }

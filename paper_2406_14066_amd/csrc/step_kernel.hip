@@ -938,12 +938,20 @@ struct PageRegs {
 constexpr int kQStride = kD * 2 + 16;   // bytes per bf16 query row in LDS
 constexpr int kOStride = kD * 4 + 16;   // bytes per fp32 output row in LDS
 
-template <int NT>
+// Wave groups.  A block's four wavefronts form WG groups of PW = 4 / WG wavefronts.  Each group
+// owns NT 16-row tiles of the query rows of one (request, KV head) and walks ALL pages of the
+// block's chunk, its PW wavefronts taking them in turn.  WG = 1 is the common case (up to 48
+// fused rows).  With more rows per KV head (long drafts on wide query groups: up to 9 x 16 = 144
+// rows) the groups of one block read the same pages at the same time, so the pages cross the
+// memory interface once and the groups find each other's loads in the compute unit's cache or
+// in flight.
+template <int NT, int WG>
 struct AttnShared {
+    static constexpr int kRowsMax = WG * NT * 16;
     union {
-        f32x4 acc[2][NT][8][kWave];               // epilogue: partial results of wavefronts 2, 3, then 1
-        unsigned char q[NT * 16 * kQStride];      // prologue: the block's query rows
-        unsigned char o[NT * 16 * kOStride];      // epilogue of an unsplit request: the output tile
+        f32x4 acc[2][NT][8][kWave];               // epilogue: partial results of the wavefronts being merged
+        unsigned char q[kRowsMax * kQStride];     // prologue: the block's query rows
+        unsigned char o[WG == 1 ? NT * 16 * kOStride : 16];   // epilogue of an unsplit request (one group): the output tile
     };
     float m[2][NT][kWave];
     float l[2][NT][kWave];
@@ -960,11 +968,14 @@ struct OrderTable {
     uniform_u32_ptr pairs;
 };
 
-template <int NT, bool SPLIT_P>
-__device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order, int item, AttnShared<NT> &sh)
+template <int NT, int WG, bool SPLIT_P>
+__device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order, int item, AttnShared<NT, WG> &sh)
 {
+    constexpr int PW = kWaves / WG;   // wavefronts that share the pages of a group between them
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int grp = wave / PW;        // this wavefront's row group
+    const int pw = wave % PW;         // ... and its place in the page walk of the group
     const int lane = tid & 63;
     const int n16 = lane & 15;
     const int g = lane >> 4;
@@ -973,29 +984,10 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
     // gets the same mix of chunk indices; the chunk indices that only the longest requests
     // have come last (blocks of the others for these indices exit at once), instead of
     // always falling on the same XCDs.
-    // With more than three row tiles per KV head (row_groups > 1) the rows of a (request, KV
-    // head, chunk) are spread over row_groups blocks of up to NT tiles each.  They sit 8 items
-    // apart, i.e. on the same XCD and dispatched one right after the other, so that the pages
-    // the first of them pulls from memory are found in that XCD's L2 by the others: K and V
-    // still cross the memory interface once.
     const int n_units = p.B * p.Hkv;
-    int chunk, kvh, b, rg = 0;   // b: rank in the order of the attention items
-    if (p.row_groups > 1) {
-        const int unit_rows = (n_units + kXcds - 1) / kXcds;
-        const int col = item % kXcds;
-        int t = item / kXcds;
-        rg = t % p.row_groups;
-        t /= p.row_groups;
-        const int urank = (t % unit_rows) * kXcds + col;
-        chunk = t / unit_rows;
-        if (urank >= n_units) return;   // padding of the last row of units
-        kvh = urank % p.Hkv;
-        b = urank / p.Hkv;
-    } else {
-        chunk = item / n_units;
-        kvh = (item % n_units) % p.Hkv;
-        b = (item % n_units) / p.Hkv;
-    }
+    const int chunk = item / n_units;
+    const int kvh = (item % n_units) % p.Hkv;
+    int b = (item % n_units) / p.Hkv;   // rank in the order of the attention items
     if (order.n > 0) {
         const uint32_t pair = order.pairs[b >> 1];
         b = (int)((b & 1) ? pair >> 16 : pair & 0xFFFFu);
@@ -1005,8 +997,8 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
     // When no request is split, a wavefront's block-table entries do not depend on kv_len:
     // fetch them alongside it (entries past the request's pages are never used).
     int bt = 0;
-    if (p.max_chunks == 1 && wave + kWaves * lane < p.max_blocks_per_req)
-        bt = p.block_table[(size_t)b * p.max_blocks_per_req + wave + kWaves * lane];
+    if (p.max_chunks == 1 && pw + PW * lane < p.max_blocks_per_req)
+        bt = p.block_table[(size_t)b * p.max_blocks_per_req + pw + PW * lane];
     const int L = uniform_load(p.kv_len, b);
     const int row0 = uniform_load(p.cu_q_len, b);
     const int q_len = uniform_load(p.cu_q_len, b + 1) - row0;
@@ -1014,7 +1006,7 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
     // whose lengths do not fit the launch (longer than planned for, beyond its block-table row,
     // shorter than its own query rows) is left out and reported.
     if (!request_lengths_ok(L, q_len, p.capacity_tokens, p.max_blocks_per_req)) {
-        if (chunk == 0 && kvh == 0 && rg == 0 && tid == 0 && p.errors != nullptr) atomicAdd(p.errors, 1ull);
+        if (chunk == 0 && kvh == 0 && tid == 0 && p.errors != nullptr) atomicAdd(p.errors, 1ull);
         return;
     }
     const int nchunks = (L + p.chunk_tokens - 1) / p.chunk_tokens;   // <= max_chunks, since L <= capacity_tokens
@@ -1022,36 +1014,38 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
     // even chunks per request, page aligned (never longer than chunk_tokens)
     const int C = ((L + nchunks - 1) / nchunks + SPEC_BLOCK_SIZE - 1) & ~(SPEC_BLOCK_SIZE - 1);
     const int group = p.Hq / p.Hkv;
-    const int row_lo = rg * (NT * 16);           // first of this block's rows among the q_len * group rows
-    if (row_lo >= q_len * group) return;         // this request has no rows for this row group
-    const int rows = min(q_len * group - row_lo, NT * 16);
+    // (the plan sized WG and NT for the longest draft of the host copy of cu_q_len; should the device
+    // copy disagree, the rows beyond that are left out rather than staged out of bounds)
+    const int rows = min(q_len * group, WG * NT * 16);
+    const int row_lo = grp * (NT * 16);          // first row of this wavefront's group
+    const int grp_rows = min(max(rows - row_lo, 0), NT * 16);
     const int tok0 = chunk * C;
     const int tok1 = min(L, tok0 + C);
-    const int npages = (tok1 - tok0 + SPEC_BLOCK_SIZE - 1) / SPEC_BLOCK_SIZE;  // <= 256
+    const int npages = (tok1 - tok0 + SPEC_BLOCK_SIZE - 1) / SPEC_BLOCK_SIZE;  // <= 64 * PW
     const int page0 = tok0 / SPEC_BLOCK_SIZE;
 
-    // block-table entries of this wavefront's pages (wave, wave+4, ...), one per lane
-    if (p.max_chunks != 1 && wave + kWaves * lane < npages)
-        bt = p.block_table[(size_t)b * p.max_blocks_per_req + page0 + wave + kWaves * lane];
+    // block-table entries of this wavefront's pages (pw, pw + PW, ...), one per lane
+    if (p.max_chunks != 1 && pw + PW * lane < npages)
+        bt = p.block_table[(size_t)b * p.max_blocks_per_req + page0 + pw + PW * lane];
     {
         // an entry outside the pool is never turned into an address: the page reads as zeros
-        const bool bad = wave + kWaves * lane < npages && (unsigned)bt >= (unsigned)p.num_blocks;
+        const bool bad = pw + PW * lane < npages && (unsigned)bt >= (unsigned)p.num_blocks;
         if (bad) bt = -1;
         const unsigned long long bad_lanes = __builtin_amdgcn_ballot_w64(bad);
-        if (bad_lanes != 0 && kvh == 0 && rg == 0 && p.errors != nullptr && lane == 0)
+        if (bad_lanes != 0 && kvh == 0 && grp == 0 && p.errors != nullptr && lane == 0)
             atomicAdd(p.errors, (unsigned long long)__builtin_popcountll(bad_lanes));
     }
 
     // Q: the block fetches its query rows once, 16 bytes per thread and consecutive threads
     // along a row (the heads of a group are adjacent in memory), and leaves them in LDS
-    u32x4 qpiece[NT];
+    u32x4 qpiece[NT * WG];
 #pragma unroll
-    for (int i = 0; i < NT; ++i) {
+    for (int i = 0; i < NT * WG; ++i) {
         const int piece = tid + i * kThreads;   // 16 pieces per row
         const int r = piece >> 4, c = piece & 15;
         qpiece[i] = (u32x4){0u, 0u, 0u, 0u};
         if (r < rows) {
-            const size_t rh = (size_t)(row0 + (row_lo + r) / group) * p.Hq + kvh * group + (row_lo + r) % group;
+            const size_t rh = (size_t)(row0 + r / group) * p.Hq + kvh * group + r % group;
             qpiece[i] = *reinterpret_cast<const u32x4 *>(static_cast<const char *>(p.q) + rh * (kD * 2) + c * 16);
         }
     }
@@ -1060,10 +1054,10 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
     int out_row[NT];   // packed (token row * Hq + head) of this lane's query row, -1 if padding
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-        const int r = nt * 16 + n16;
+        const int r = row_lo + nt * 16 + n16;
         const bool valid = r < rows;
-        const int j = valid ? (row_lo + r) / group : 0;
-        const int gq = valid ? (row_lo + r) % group : 0;
+        const int j = valid ? r / group : 0;
+        const int gq = valid ? r % group : 0;
         limit[nt] = valid ? L - q_len + j : -1;
         out_row[nt] = valid ? (int)((size_t)(row0 + j) * p.Hq + kvh * group + gq) : -1;
     }
@@ -1077,7 +1071,8 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
     const char *khead = static_cast<const char *>(p.k_cache) + (size_t)kvh * kPageHeadBytes;
     const char *vhead = static_cast<const char *>(p.v_cache) + (size_t)kvh * kPageHeadBytes;
     const size_t page_stride = (size_t)p.Hkv * kPageHeadBytes;
-    const int my_pages = npages > wave ? (npages - wave + kWaves - 1) / kWaves : 0;   // pages wave, wave+4, ...
+    // pages pw, pw + PW, ... (none for a group that has no rows of this request)
+    const int my_pages = (npages > pw && grp_rows > 0) ? (npages - pw + PW - 1) / PW : 0;
     const int lane_off = lane * 16;
 
     auto load_page = [&](int it, PageRegs &r) {   // it-th page of this wavefront
@@ -1194,13 +1189,13 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
     auto consume_batch = [&](PageRegs(&r)[P], int it) {
 #pragma unroll
         for (int j = 0; j < P; ++j)
-            if (it + j < my_pages) consume(r[j], wave + kWaves * (it + j));
+            if (it + j < my_pages) consume(r[j], pw + PW * (it + j));
     };
     load_batch(0, batch_a);
 
     // Q as the B operand of S^T = K Q^T, out of LDS (the first pages are on their way)
 #pragma unroll
-    for (int i = 0; i < NT; ++i) {
+    for (int i = 0; i < NT * WG; ++i) {
         const int piece = tid + i * kThreads;
         *reinterpret_cast<u32x4 *>(sh.q + (piece >> 4) * kQStride + (piece & 15) * 16) = qpiece[i];
     }
@@ -1209,7 +1204,7 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
     for (int nt = 0; nt < NT; ++nt) {
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk)
-            qreg[nt][kk] = *reinterpret_cast<const bf16x8 *>(sh.q + (nt * 16 + n16) * kQStride + kk * 64 + g * 16);
+            qreg[nt][kk] = *reinterpret_cast<const bf16x8 *>(sh.q + (row_lo + nt * 16 + n16) * kQStride + kk * 64 + g * 16);
     }
     __syncthreads();   // the epilogue reuses this memory
 
@@ -1229,7 +1224,7 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
         l_run[nt] += __shfl_xor(l_run[nt], 32);
     }
 
-    // merge the four wavefronts: 2,3 -> 0,1 then 1 -> 0
+    // merge the wavefronts of each group into the group's first one
     auto put = [&](int buf) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
@@ -1253,39 +1248,61 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
             for (int mt = 0; mt < 8; ++mt) acc[nt][mt] = acc[nt][mt] * wa + sh.acc[buf][nt][mt][lane] * wb;
         }
     };
-    if (wave >= 2) put(wave - 2);
-    __syncthreads();
-    if (wave < 2) merge(wave);
-    __syncthreads();
-    if (wave == 1) put(0);
-    __syncthreads();
+    if constexpr (WG == 1) {          // 2,3 -> 0,1 then 1 -> 0 (the last step below, by wavefront 0)
+        if (wave >= 2) put(wave - 2);
+        __syncthreads();
+        if (wave < 2) merge(wave);
+        __syncthreads();
+        if (wave == 1) put(0);
+        __syncthreads();
+    } else if constexpr (WG == 2) {   // 1 -> 0 and 3 -> 2
+        if (pw == 1) put(grp);
+        __syncthreads();
+        if (pw == 0) merge(grp);
+        __syncthreads();
+    }
+    const bool lead = pw == 0 && grp_rows > 0;   // this wavefront holds its group's result
 
     if (nchunks == 1) {
-        // the only chunk of this (request, KV head): normalise, lay the tile out by rows in
-        // LDS, and let the whole block write the rows (16 bytes per thread, consecutive
-        // threads along a row)
-        if (wave == 0) {
-            merge(0);   // (its reads of the shared partials precede the writes below in program order)
+        if constexpr (WG == 1) {
+            // the only chunk of this (request, KV head): normalise, lay the tile out by rows in
+            // LDS, and let the whole block write the rows (16 bytes per thread, consecutive
+            // threads along a row)
+            if (wave == 0) {
+                merge(0);   // (its reads of the shared partials precede the writes below in program order)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                    const float inv = 1.0f / l_run[nt];
+#pragma unroll
+                    for (int mt = 0; mt < 8; ++mt)
+                        *reinterpret_cast<f32x4 *>(sh.o + (nt * 16 + n16) * kOStride + mt * 64 + g * 16) = acc[nt][mt] * inv;
+                }
+            }
+            __syncthreads();
+            for (int piece = tid; piece < rows * 32; piece += kThreads) {   // 32 pieces per row
+                const int r = piece >> 5, c = piece & 31;
+                const size_t rh = (size_t)(row0 + r / group) * p.Hq + kvh * group + r % group;
+                __builtin_nontemporal_store(*reinterpret_cast<const f32x4 *>(sh.o + r * kOStride + c * 16),
+                                            reinterpret_cast<f32x4 *>(p.out + rh * kD + c * 4));
+            }
+        } else if (lead) {
+            // several groups: each group's first wavefront writes its rows itself (a lane holds four
+            // consecutive head dims of one row per 16-dim slice)
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
+                if (out_row[nt] < 0) continue;
                 const float inv = 1.0f / l_run[nt];
 #pragma unroll
                 for (int mt = 0; mt < 8; ++mt)
-                    *reinterpret_cast<f32x4 *>(sh.o + (nt * 16 + n16) * kOStride + mt * 64 + g * 16) = acc[nt][mt] * inv;
+                    __builtin_nontemporal_store(acc[nt][mt] * inv,
+                                                reinterpret_cast<f32x4 *>(p.out + (size_t)out_row[nt] * kD + mt * 16 + 4 * g));
             }
-        }
-        __syncthreads();
-        for (int piece = tid; piece < rows * 32; piece += kThreads) {   // 32 pieces per row
-            const int r = piece >> 5, c = piece & 31;
-            const size_t rh = (size_t)(row0 + (row_lo + r) / group) * p.Hq + kvh * group + (row_lo + r) % group;
-            __builtin_nontemporal_store(*reinterpret_cast<const f32x4 *>(sh.o + r * kOStride + c * 16),
-                                        reinterpret_cast<f32x4 *>(p.out + rh * kD + c * 4));
         }
         return;
     }
 
-    if (wave == 0) {
-        merge(0);
+    if (WG == 1 ? wave == 0 : lead) {
+        if constexpr (WG == 1) merge(0);
         // one partial per query row: acc[dim], running max, running sum
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
@@ -1300,17 +1317,17 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
             if (g == 0)
                 publish_u64(reinterpret_cast<unsigned long long *>(p.ws_ml + slot * 2), pack_f32x2(m_run[nt], l_run[nt]));
         }
-        if (!p.fused_combine) return;   // a separate combine launch merges the partials
-        writes_complete();  // the partial is in memory before the ticket is taken
-        if (lane == 0) {
-            unsigned long long *ticket = &p.tickets[(size_t)unit * p.row_groups + rg];
-            const uint32_t before = ticket_arrive(ticket, p.generation);
-            const int last = (before + 1u == (uint32_t)nchunks) ? 1 : 0;
-            if (last) ticket_reset(ticket);
-            sh.last = last;
-        }
+        writes_complete();  // the partials are in memory before the ticket is taken
     }
-    if (!p.fused_combine) return;
+    if (!p.fused_combine) return;   // a separate combine launch merges the partials
+    if constexpr (WG > 1) __syncthreads();   // ... those of every group
+    if (tid == 0) {
+        unsigned long long *ticket = &p.tickets[unit];
+        const uint32_t before = ticket_arrive(ticket, p.generation);
+        const int last = (before + 1u == (uint32_t)nchunks) ? 1 : 0;
+        if (last) ticket_reset(ticket);
+        sh.last = last;
+    }
     __syncthreads();
     if (!sh.last) return;
     order_after_ticket();
@@ -1332,7 +1349,7 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
         for (int j = 0; j < RB; ++j) {
             const int r = r0 + 2 * kWaves * j;
             rv[j] = r < rows;
-            const int rr = row_lo + (rv[j] ? r : 0);
+            const int rr = rv[j] ? r : 0;
             rh[j] = (size_t)(row0 + rr / group) * p.Hq + kvh * group + rr % group;
             const size_t base = rh[j] * p.max_chunks;
             ml[j] = reinterpret_cast<const unsigned long long *>(p.ws_ml) + base;
@@ -1415,7 +1432,7 @@ struct StepArgs {
     UnitOrder order;
 };
 
-template <int NT, bool HAS_ATTN, bool HAS_REJECT, bool SPLIT_P>
+template <int NT, int WG, bool HAS_ATTN, bool HAS_REJECT, bool SPLIT_P>
 __global__ __launch_bounds__(kThreads, 2) void spec_step_kernel(StepArgs args)
 {
     const AttnParams &ap = args.ap;
@@ -1478,16 +1495,16 @@ __global__ __launch_bounds__(kThreads, 2) void spec_step_kernel(StepArgs args)
         }
     }
     if constexpr (HAS_ATTN) {
-        __shared__ AttnShared<NT> ash;
+        __shared__ AttnShared<NT, WG> ash;
         OrderTable order;
         order.n = args.order.n;
         order.pairs = (uniform_u32_ptr)((const char __attribute__((address_space(4))) *)__builtin_amdgcn_kernarg_segment_ptr() +
                                         offsetof(StepArgs, order) + offsetof(UnitOrder, request));
-        attn_role<NT, SPLIT_P>(ap, order, item, ash);
+        attn_role<NT, WG, SPLIT_P>(ap, order, item, ash);
     }
 }
 
-template <int NT, bool HAS_ATTN, bool HAS_REJECT>
+template <int NT, int WG, bool HAS_ATTN, bool HAS_REJECT>
 hipError_t launch(const AttnParams &ap, const RejectParams &rp, int n_stat, int n_attn, int n_race,
                   const UnitOrder *order, LaunchEvents ev, hipStream_t stream)
 {
@@ -1524,19 +1541,22 @@ hipError_t launch(const AttnParams &ap, const RejectParams &rp, int n_stat, int 
     const dim3 grid(mixed ? (rows_attn_all + rows_reject) * kXcds
                           : (HAS_ATTN && HAS_REJECT ? (rows_attn_all + rows_reject) * kXcds : n_reject + n_attn));
     // (with events the extended launch attaches them to the kernel's own begin and end)
-    if (HAS_ATTN && !ap.split_p) {
-        if (ev.start != nullptr)
-            hipExtLaunchKernelGGL((spec_step_kernel<NT, HAS_ATTN, HAS_REJECT, false>), grid, dim3(kThreads), 0, stream,
-                                  ev.start, ev.stop, 0, args);
-        else
-            hipLaunchKernelGGL((spec_step_kernel<NT, HAS_ATTN, HAS_REJECT, false>), grid, dim3(kThreads), 0, stream, args);
-    } else {
-        if (ev.start != nullptr)
-            hipExtLaunchKernelGGL((spec_step_kernel<NT, HAS_ATTN, HAS_REJECT, true>), grid, dim3(kThreads), 0, stream,
-                                  ev.start, ev.stop, 0, args);
-        else
-            hipLaunchKernelGGL((spec_step_kernel<NT, HAS_ATTN, HAS_REJECT, true>), grid, dim3(kThreads), 0, stream, args);
+    // The variant that feeds the softmax weights as one bf16 (an experiment switch) exists for one wave group only.
+    if constexpr (WG == 1) {
+        if (HAS_ATTN && !ap.split_p) {
+            if (ev.start != nullptr)
+                hipExtLaunchKernelGGL((spec_step_kernel<NT, WG, HAS_ATTN, HAS_REJECT, false>), grid, dim3(kThreads), 0, stream,
+                                      ev.start, ev.stop, 0, args);
+            else
+                hipLaunchKernelGGL((spec_step_kernel<NT, WG, HAS_ATTN, HAS_REJECT, false>), grid, dim3(kThreads), 0, stream, args);
+            return hipGetLastError();
+        }
     }
+    if (ev.start != nullptr)
+        hipExtLaunchKernelGGL((spec_step_kernel<NT, WG, HAS_ATTN, HAS_REJECT, true>), grid, dim3(kThreads), 0, stream,
+                              ev.start, ev.stop, 0, args);
+    else
+        hipLaunchKernelGGL((spec_step_kernel<NT, WG, HAS_ATTN, HAS_REJECT, true>), grid, dim3(kThreads), 0, stream, args);
     return hipGetLastError();
 }
 
@@ -1544,9 +1564,7 @@ hipError_t launch(const AttnParams &ap, const RejectParams &rp, int n_stat, int 
 
 int step_attn_items(const AttnParams &ap)
 {
-    const int n_units = ap.B * ap.Hkv;
-    if (ap.row_groups > 1) return (n_units + kXcds - 1) / kXcds * kXcds * ap.row_groups * ap.max_chunks;
-    return n_units * ap.max_chunks;
+    return ap.B * ap.Hkv * ap.max_chunks;
 }
 
 hipError_t launch_step_fused(const AttnParams *attn, int row_tiles, const RejectParams *reject, const UnitOrder *order,
@@ -1565,25 +1583,30 @@ hipError_t launch_step_fused(const AttnParams *attn, int row_tiles, const Reject
     }
     if (attn != nullptr) {
         ap = *attn;
-        if (ap.d != kD || ap.chunk_tokens > 4096 || ap.chunk_tokens % SPEC_BLOCK_SIZE != 0 || row_tiles < 1 ||
-            row_tiles > 3 || ap.row_groups < 1 || ap.capacity_tokens > ap.chunk_tokens * ap.max_chunks ||
+        // tiles per wave group and wave groups per block that the kernel is built for
+        const bool shape_ok = (ap.row_groups == 1 && row_tiles >= 1 && row_tiles <= 3) ||
+                              ((ap.row_groups == 2 || ap.row_groups == 4) && (row_tiles == 2 || row_tiles == 3));
+        // (a wavefront keeps the block-table entries of its pages one per lane)
+        if (ap.d != kD || !shape_ok || ap.chunk_tokens > 4096 / ap.row_groups || ap.chunk_tokens % SPEC_BLOCK_SIZE != 0 ||
+            ap.capacity_tokens > ap.chunk_tokens * ap.max_chunks ||
             (ap.fused_combine && ap.max_chunks > kMaxFusedChunks) || (order != nullptr && order->n != 0 && order->n != ap.B))
             return hipErrorInvalidValue;
         n_attn = step_attn_items(ap);
     }
-    if (attn == nullptr) return launch<1, false, true>(ap, rp, n_stat, 0, n_race, nullptr, ev, stream);
-    if (reject == nullptr) {
-        switch (row_tiles) {
-            case 1: return launch<1, true, false>(ap, rp, 0, n_attn, 0, order, ev, stream);
-            case 2: return launch<2, true, false>(ap, rp, 0, n_attn, 0, order, ev, stream);
-            default: return launch<3, true, false>(ap, rp, 0, n_attn, 0, order, ev, stream);
-        }
+    if (attn == nullptr) return launch<1, 1, false, true>(ap, rp, n_stat, 0, n_race, nullptr, ev, stream);
+#define SPEC_LAUNCH_ATTN(NT_, WG_)                                                                              \
+    (reject == nullptr ? launch<NT_, WG_, true, false>(ap, rp, 0, n_attn, 0, order, ev, stream)                 \
+                       : launch<NT_, WG_, true, true>(ap, rp, n_stat, n_attn, n_race, order, ev, stream))
+    switch (ap.row_groups * 10 + row_tiles) {
+        case 11: return SPEC_LAUNCH_ATTN(1, 1);
+        case 12: return SPEC_LAUNCH_ATTN(2, 1);
+        case 13: return SPEC_LAUNCH_ATTN(3, 1);
+        case 22: return SPEC_LAUNCH_ATTN(2, 2);
+        case 23: return SPEC_LAUNCH_ATTN(3, 2);
+        case 42: return SPEC_LAUNCH_ATTN(2, 4);
+        default: return SPEC_LAUNCH_ATTN(3, 4);
     }
-    switch (row_tiles) {
-        case 1: return launch<1, true, true>(ap, rp, n_stat, n_attn, n_race, order, ev, stream);
-        case 2: return launch<2, true, true>(ap, rp, n_stat, n_attn, n_race, order, ev, stream);
-        default: return launch<3, true, true>(ap, rp, n_stat, n_attn, n_race, order, ev, stream);
-    }
+#undef SPEC_LAUNCH_ATTN
 }
 
 }  // namespace specv

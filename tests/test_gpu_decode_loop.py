@@ -21,8 +21,8 @@ def _bf16_dev(a, dev):
 
 
 @pytest.mark.parametrize("Hq,Hkv,k,start", [
-    (8, 2, 3, [60, 125, 250, 700, 1000, 62]),          # one block per (request, KV head, chunk)
-    (32, 2, 4, [63, 1279, 15, 640]),                   # 80 rows per KV head: two blocks per (request, KV head, chunk)
+    (8, 2, 3, [60, 125, 250, 700, 1000, 62]),          # 16 rows per KV head: one wave group
+    (32, 2, 4, [63, 1279, 15, 640]),                   # 80 rows per KV head: two wave groups per block
 ], ids=["gqa4_k3", "gqa16_k4_row_groups"])
 def test_captured_step_survives_a_decode_loop(Hq, Hkv, k, start):
     import torch

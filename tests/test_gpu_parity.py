@@ -48,13 +48,14 @@ SMALL = [
     ("many_rows", dict(B=2, Hq=16, Hkv=2, d=128, kv_len=[129, 400], k=[8, 6])),   # 72 rows per KV head
 ]
 
-# more than 48 fused rows per KV head: several blocks per (request, KV head, chunk) on the matrix path
+# more than 48 fused rows per KV head: the block's wavefronts split the rows (2 or 4 wave groups) on the matrix path
 ROW_GROUP_CASES = [
-    # name, kwargs, row tiles per block, blocks per (request, KV head, chunk)
+    # name, kwargs, row tiles per wave group, wave groups per block
     ("g8_k8_k6", dict(B=2, Hq=16, Hkv=2, d=128, kv_len=[129, 400], k=[8, 6]), 3, 2),          # 72 and 56 rows
     ("g8_k7_split", dict(B=3, Hq=16, Hkv=2, d=128, kv_len=[3000, 517, 1999], k=[7, 7, 7]), 2, 2),   # 64 rows, requests split into chunks
-    ("g16_k8", dict(B=2, Hq=16, Hkv=1, d=128, kv_len=[700, 90], k=[8, 8]), 3, 3),             # 144 rows
-    ("g16_ragged_k", dict(B=5, Hq=32, Hkv=2, d=128, kv_len=[64, 1500, 9, 333, 2048], k=[8, 0, 3, 5, 2]), 3, 3),  # requests with 1, 2 and 3 groups' worth of rows
+    ("g16_k8", dict(B=2, Hq=16, Hkv=1, d=128, kv_len=[700, 90], k=[8, 8]), 3, 4),             # 144 rows
+    ("g16_k6_long", dict(B=2, Hq=16, Hkv=1, d=128, kv_len=[5000, 1300], k=[6, 6]), 2, 4),     # 112 rows, chunks of at most 1024 tokens
+    ("g16_ragged_k", dict(B=5, Hq=32, Hkv=2, d=128, kv_len=[64, 1500, 9, 333, 2048], k=[8, 0, 3, 5, 2]), 3, 4),  # requests that fill 1, 2 and 4 groups
     ("c4_shape_k7", dict(B=20, Hq=64, Hkv=8, d=128, kv_len=[256 + 37 * i for i in range(20)], k=[7] * 20), 2, 2),
 ]
 

@@ -322,10 +322,11 @@ def test_bucket_plan_does_not_depend_on_the_lengths():
     (64, 8, 2, sv.PATH_MFMA, 2, 1),      # 24 rows
     (32, 8, 8, sv.PATH_MFMA, 3, 1),      # 36 rows
     (64, 8, 5, sv.PATH_MFMA, 3, 1),      # 48 rows
-    (64, 8, 6, sv.PATH_MFMA, 2, 2),      # 56 rows: two blocks of two tiles
+    (64, 8, 6, sv.PATH_MFMA, 2, 2),      # 56 rows: two wave groups of two tiles
     (64, 8, 7, sv.PATH_MFMA, 2, 2),      # 64 rows
     (64, 8, 8, sv.PATH_MFMA, 3, 2),      # 72 rows
-    (16, 1, 8, sv.PATH_MFMA, 3, 3),      # 144 rows: the widest group at the longest draft
+    (16, 1, 6, sv.PATH_MFMA, 2, 4),      # 112 rows: four wave groups
+    (16, 1, 8, sv.PATH_MFMA, 3, 4),      # 144 rows: the widest group at the longest draft
     (16, 1, 3, sv.PATH_MFMA, 2, 2),      # 64 rows
 ])
 def test_every_supported_row_count_takes_the_matrix_path(Hq, Hkv, k, path, tiles, groups):
