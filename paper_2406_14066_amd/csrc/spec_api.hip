@@ -404,10 +404,11 @@ RejectPlan plan_reject(const spec_reject_args *r, size_t base, const Tuning &tu,
     // Early stop: with one draft length for all requests the statistics items can be taken in
     // position order and the rows after a request's first rejection left unread.  That turns the
     // pass into a chain of k+1 dependent stages (about 12 us each, then the race), which must stay
-    // hidden: under an attention half that takes clearly longer than the chain, or, when the
-    // rejection half runs alone, behind several rounds of blocks per position.  Measured (step
-    // with / without): B=256 k=2 (64/8 heads) -4%, B=64 k=8 (32/32 heads, L=1024) -8%, B=64 k=4 -3%,
-    // B=32 k=1..3 -2%, B=32 k=4 +2%, B=32 k=8 +16%, B=16 k=2 (L=2048) +2%, B=8 k=4 +32%.
+    // hidden: under a launch that streams (KV and logit bytes at 5.5 TB/s) for clearly longer than
+    // the chain takes, or, when the rejection half runs alone, behind several rounds of blocks per
+    // position.  Measured (step with / without): B=256 k=2 (64/8 heads) -4%, the same at k=7 -15%,
+    // B=64 k=8 (32/32 heads, L=1024) -8%, B=64 k=4 -3%, B=32 k=1..3 -2%, B=32 k=4 +2%, B=32 k=8 +16%,
+    // B=16 k=2 (L=2048) +2%, B=8 k=4 +32%.
     pl.early_stop = 0;
     pl.uniform_k = 0;
     if (r->T > r->B && r->T % r->B == 0) {
@@ -416,7 +417,8 @@ RejectPlan plan_reject(const spec_reject_args *r, size_t base, const Tuning &tu,
         for (int b = 0; b < r->B && uniform; ++b) uniform = r->host_cu_q_len[b + 1] - r->host_cu_q_len[b] == q;
         bool wanted;
         if (attn_us >= 0.0) {
-            wanted = r->B >= 32 && 12.0 * q + 30.0 <= 0.85 * attn_us;
+            const double logits_us = (double)rows * r->V * 4.0 / 5.5e6;
+            wanted = r->B >= 32 && 12.0 * q + 30.0 <= 0.85 * (attn_us + logits_us);
         } else {
             const int64_t per_position = (int64_t)(r->accept_mode == SPEC_ACCEPT_SAMPLE ? 2 : 1) * r->B * pl.stat_segments;
             wanted = (int64_t)rows * pl.stat_segments >= 3ll * compute_units() && per_position >= compute_units();
