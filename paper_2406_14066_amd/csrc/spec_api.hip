@@ -458,7 +458,7 @@ void make_order(const spec_attn_args *a, UnitOrder &order)
 
 // ---------------------------------------------------------------------------
 // Plan cache: what one shape needs beyond the scalar checks, keyed by a hash of everything the
-// plan depends on.  Per thread, a handful of entries, replaced in turn.
+// plan depends on.  Per thread, sixteen entries (one per draft length and then some), replaced in turn.
 // ---------------------------------------------------------------------------
 struct StepPlan {
     uint64_t key = 0;
@@ -508,7 +508,7 @@ uint64_t plan_key(const spec_attn_args *a, const spec_reject_args *r, const Tuni
     return h | 1ull;
 }
 
-constexpr int kPlanCacheEntries = 8;
+constexpr int kPlanCacheEntries = 16;
 struct PlanCache {
     StepPlan entry[kPlanCacheEntries];
     int next = 0;
