@@ -84,6 +84,31 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Exchanges between the four 16-lane rows of a wavefront with the gfx950 row-swap instructions
+// (vector ALU, a few cycles) instead of a round trip through the LDS crossbar, which is what a
+// generic lane shuffle by 16 or 32 compiles to: v_permlane16_swap trades the odd rows of its
+// first operand with the even rows of its second, v_permlane32_swap the upper half of the first
+// with the lower half of the second.  Fed the same value twice, the two results hold, in every
+// lane l, the values of lanes l and l ^ 16 (l ^ 32).
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float max_across_xor16(float v)
+{
+    const u32x2_t r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float max_across_xor32(float v)
+{
+    const u32x2_t r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float sum_across_rows(float v)   // over lanes l, l ^ 16, l ^ 32, l ^ 48
+{
+    u32x2_t r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    v = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 // 16 bytes of logits that this launch will not read again (see kStreamPolicy).
 __device__ __forceinline__ float4 load_streaming(const float *p)
 {
@@ -1136,8 +1161,7 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
                     if (tbase + r > limit[nt]) s[r] = -INFINITY;
             }
             float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
-            mx = fmaxf(mx, __shfl_xor(mx, 16));
-            mx = fmaxf(mx, __shfl_xor(mx, 32)) * p.scale_log2;
+            mx = max_across_xor32(max_across_xor16(mx)) * p.scale_log2;
             // The reference of the running sums follows the maximum lazily: it is raised only when
             // a score exceeds it by more than 8 (base-2 units), so weights reach at most 2^8 and
             // the accumulators are rescaled on few pages instead of on most early ones (the
@@ -1220,8 +1244,7 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
     // each lane summed its own four tokens per page: finish the row sums
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-        l_run[nt] += __shfl_xor(l_run[nt], 16);
-        l_run[nt] += __shfl_xor(l_run[nt], 32);
+        l_run[nt] = sum_across_rows(l_run[nt]);
     }
 
     // merge the wavefronts of each group into the group's first one
