@@ -119,3 +119,26 @@ def test_workspace_reused_across_shapes(harness):
             res = s.results()
             check_attn(w, res["out"])
             check_reject(w, res)
+
+
+@pytest.mark.parametrize("kw,chunk", [
+    (dict(B=1, Hq=4, Hkv=1, d=128, kv_len=[8197], k=[3]), None),             # one unit split into more than 64 chunks by the planner
+    (dict(B=2, Hq=8, Hkv=2, d=128, kv_len=[4500, 300], k=[2, 5]), 64),       # ... and by the chunk-size switch, beside an unsplit request
+], ids=["planner", "switch"])
+def test_more_than_64_chunks_take_the_separate_merge_launch(harness, tuning, kw, chunk):
+    """The matrix kernel's last-arriver merge handles up to 64 chunks per request; beyond that the
+    partials are merged by a launch of their own."""
+    print("case many chunks", kw["kv_len"], chunk, flush=True)
+    if chunk:
+        tuning("SPEC_VERIFY_CHUNK", chunk)
+    w = W.make_workload("chunks", V=64, dtype="bf16", draft_std=2.0, sigma=1.0, data_seed=31, philox_seed=8, **kw)
+    ds = harness.DeviceStep(w, kv_layout=sv.KV_MFMA)
+    plan = ds.plan()
+    assert plan["attn_path"] == sv.PATH_MFMA and plan["max_chunks"] > 64 and plan["launches"] == 2, plan
+    ds.run_step()
+    res = ds.results()
+    check_attn(w, res["out"])
+    check_reject(w, res)
+    ds.out.fill_(float("nan"))
+    ds.run_attn()
+    check_attn(w, ds.results()["out"])
