@@ -329,11 +329,12 @@ AttnPlan plan_attn(const spec_attn_args *a, const Tuning &tu)
         // Splitting costs (partials, a merge, more block start-ups), so the longest request is split
         // only as far as needed to give every compute unit a block.  With three row tiles the
         // wavefronts spend a larger share of their time on arithmetic and need a second block beside
-        // them to keep loads in flight: then the target is two blocks per compute unit, less a
-        // sixteenth of the slots, which the rejection items flow through while the attention blocks
-        // (all resident from the start) stream.
+        // them to keep loads in flight: then the target is two blocks per compute unit, less an
+        // eighth of the slots, which the rejection items flow through while the attention blocks
+        // (all resident from the start) stream (with a sixteenth the rejection items of the ragged
+        // long-context workload ended after the attention: 90.0 against 88.2 us).
         const long cus = compute_units();
-        long target_blocks = pl.row_tiles >= 3 ? 2 * cus - cus / 8 : cus;
+        long target_blocks = pl.row_tiles >= 3 ? 2 * cus - cus / 4 : cus;
         if (tu.target_blocks > 0) target_blocks = tu.target_blocks;
         const int64_t units = (int64_t)a->B * a->Hkv;
         int64_t nsplit = (target_blocks + units - 1) / units;

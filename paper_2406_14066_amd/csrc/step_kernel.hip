@@ -1149,6 +1149,7 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
 
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
+            if (nt > 0 && nt * 16 >= grp_rows) continue;   // a tile this request has no rows for (the same for the whole wavefront)
             f32x4 s = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk)
@@ -1359,7 +1360,7 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
     // Half a wavefront takes two query rows at a time (four head dims per lane) and eight
     // chunks of each per pass; every load of a pass is issued before the first is used, so
     // a pass costs one memory round trip.
-    constexpr int GROUP = 8;   // chunks merged per pass
+    constexpr int GROUP = 8;   // chunks merged per pass (16 per pass spill 200 to 340 bytes per lane)
     constexpr int RB = NT >= 2 ? 2 : 1;   // rows in flight per half wavefront (one row tile: at most two passes anyway, and registers are tight)
     const int half = lane >> 5, l32 = lane & 31;
     for (int r0 = 2 * wave + half; r0 < rows; r0 += 2 * kWaves * RB) {
