@@ -39,7 +39,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c4", choices=["c2", "c3", "c4", "c5", "c4_k7"],
+    ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4", "c5", "c4_k7"],
                     help="the workload of the headline figures")
     ap.add_argument("--k", type=int, default=None, help="speculation length of the c3 sweep point")
     ap.add_argument("--alpha", type=float, default=None, help="acceptance level of the c3 sweep point")
@@ -82,8 +82,9 @@ def make_workload(name, k=None, alpha=None):
 
 
 def describe(w):
-    return ("%s: B=%d, L=%s, k=%s, Hq/Hkv=%d/%d, d=%d, bf16 paged KV (block 16, shuffled table), V=%d fp32 logits"
-            % (w.name, w.B, _span(w.kv_len), _span(w.k), w.Hq, w.Hkv, w.d, w.V))
+    kv = "bf16 paged KV (block 16, shuffled table)" if w.dtype == "bf16" else "fp32 KV (8 consecutive pages of 16)"
+    return ("%s: B=%d, L=%s, k=%s, Hq/Hkv=%d/%d, d=%d, %s, V=%d fp32 logits"
+            % (w.name, w.B, _span(w.kv_len), _span(w.k), w.Hq, w.Hkv, w.d, kv, w.V))
 
 
 def measure(w, args, mode, with_graph):
@@ -92,7 +93,9 @@ def measure(w, args, mode, with_graph):
     from paper_2406_14066_amd import spec_verify as sv
     from paper_2406_14066_amd.harness import DeviceStep
 
-    ds = DeviceStep(w, kv_layout=sv.KV_MFMA, with_debug=False, accept_mode=mode)
+    # bf16 workloads keep their pages in the matrix-operand layout; the tiny fp32 one (c1) has token-major pages
+    layout = sv.KV_MFMA if w.dtype == "bf16" else sv.KV_TOKEN_MAJOR
+    ds = DeviceStep(w, kv_layout=layout, with_debug=False, accept_mode=mode)
     plan = ds.plan()
     attn_bytes = w.attn_algorithmic_bytes()
     # without a draft distribution only the target rows are read
@@ -151,24 +154,40 @@ def measure(w, args, mode, with_graph):
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         graph = torch.cuda.CUDAGraph()
+        per_graph = -(-max(args.steps, 1) // nrot) * nrot     # K steps rounded up to whole rounds of the rotated copies
         with torch.cuda.graph(graph, stream=side):
-            for a, r in variants:
+            for i in range(per_graph):
+                a, r = variants[i % nrot]
                 sv.spec_verify_step(a, r, ds.workspace, torch.cuda.current_stream())
         torch.cuda.synchronize()
-        replays = max(args.steps // nrot, 1)
-        for _ in range(max(args.warmup // nrot, 1)):
-            graph.replay()
+        replays = 3
+        graph.replay()
         torch.cuda.synchronize()
         g0 = time.perf_counter()
         for _ in range(replays):
             graph.replay()
         torch.cuda.synchronize()
         g1 = time.perf_counter()
-        graph_sec = (g1 - g0) / (replays * nrot)
+        graph_sec = (g1 - g0) / (replays * per_graph)
         graph_info = {"ms_per_step": graph_sec * 1e3, "value": w.verified_tokens() / graph_sec,
-                      "steps": replays * nrot, "steps_per_graph": nrot,
+                      "steps": replays * per_graph, "steps_per_graph": per_graph,
                       "achieved_GBps": step_bytes / graph_sec / 1e9}
         del graph
+    # the step before the path: this step's K/V rows entering the paged cache (same positions every time)
+    append_us = None
+    if w.dtype == "bf16":
+        nk = torch.randn((w.T, w.Hkv, w.d), device="cuda").to(torch.bfloat16)
+        nv = torch.randn((w.T, w.Hkv, w.d), device="cuda").to(torch.bfloat16)
+        reps = max(args.steps, 10)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for i in range(reps + 3):
+            if i == 3:
+                e0.record()
+            sv.spec_kv_append(nk, nv, ds.k_cache, ds.v_cache, ds.block_table, ds.kv_len, ds.cu_q_len, w.kv_len, w.cu_q_len,
+                              kv_layout=layout)
+        e1.record()
+        torch.cuda.synchronize()
+        append_us = e0.elapsed_time(e1) * 1e3 / reps
     res = ds.results()
     calls = max(int(res["counters"][5]) // w.B, 1)
     emitted_per_step = int(res["counters"][3]) // calls
@@ -181,14 +200,16 @@ def measure(w, args, mode, with_graph):
     rej_bytes_needed = int(rows_needed.sum()) * w.V * 4
 
     kernel_us = {k: (1e3 * ms / n if n else None) for k, (ms, n) in kt.items()}
-    # the step is the one launch of the step kernel (plus a merge launch only when a request has more than 64 chunks)
-    step_us = kernel_us["step"] + (kernel_us["attn_combine"] or 0.0)
+    # the step is the one launch of the step kernel (plus a merge launch only when a request has more than 64
+    # chunks); on the generic path (fp32) it is three launches: attention partials, their merge, rejection sampling
+    step_us = sum(kernel_us[k] or 0.0 for k in ("step", "attn_generic", "attn_combine", "reject"))
     achieved = step_bytes / (step_us * 1e-6) / 1e9
     out = dict(
         w=w, ds=ds, res=res, plan=plan, nrot=nrot, sec_per_step=sec_per_step, sec_per_step_events=sec_per_step_events,
         host_us_per_call=(t_enqueued - t0) / args.steps * 1e6, kernel_us=kernel_us, step_us=step_us, achieved=achieved,
         attn_bytes=attn_bytes, rej_bytes=rej_bytes, step_bytes=step_bytes, rej_bytes_needed=rej_bytes_needed,
         emitted_per_step=emitted_per_step, graph_info=graph_info, events_in_region=events_in_region,
+        kv_append_us=append_us,
         near_tie_accept_tests_per_step=int(res["counters"][4]) // calls,
         input_errors=int(res["counters"][6]), abandoned=int(res["counters"][7]),
     )
@@ -238,7 +259,7 @@ def main():
     # the other workloads first (each frees its device memory before the next), the headline one last
     others = {}
     if not args.only:
-        for name, kw in [("c2", {}), ("c3", dict(k=4, alpha=0.7)), ("c5", {}), ("c4_k7", {})]:
+        for name, kw in [("c1", {}), ("c2", {}), ("c3", dict(k=4, alpha=0.7)), ("c5", {}), ("c4_k7", {})]:
             if name == args.workload:
                 continue
             wo = make_workload(name, **kw)
@@ -284,6 +305,7 @@ def main():
         },
         "kernel_us": mm["kernel_us"],
         "host_us_per_call": mm["host_us_per_call"],
+        "kv_append_us_per_call": mm["kv_append_us"],   # back-to-back launches of spec_kv_append for this step's T rows
         "graph_replay": mm["graph_info"],
         "decisions": {
             # counters[4]: evaluated accept tests within 1e-6 of their uniform, per step (counted by the kernel)

@@ -279,7 +279,8 @@ spec_status spec_validate_reject(const spec_reject_args *reject);
  * kv_len[b] - q_len[b] + j of request b, through the block table, in the given
  * page layout.  Everything else in the pools is left as it is.  Device pointers;
  * host_kv_len / host_cu_q_len are HOST copies used for validation only.
- * SPEC_EINVAL if a position falls outside the request's block-table row.
+ * SPEC_EINVAL if a position falls outside the request's block-table row, or if new_k, new_v or
+ * a pool is not 32-byte aligned (rows move as vectors of 8 elements).
  */
 typedef struct {
     int32_t B, Hkv, d, num_blocks, max_blocks_per_req, T;

@@ -224,11 +224,16 @@ __global__ void kv_append_kernel(KvAppendParams p)
     const T *sv = static_cast<const T *>(p.new_v) + ((size_t)row * p.Hkv + kvh) * p.d + g * 8;
     T *dk = static_cast<T *>(p.k_cache);
     T *dv = static_cast<T *>(p.v_cache);
+    // the 8 elements of a thread are contiguous in the cache in every case but one (V in the tiled
+    // layout, where consecutive dims of a token are 16 bytes apart): whole-vector stores where they are
+    struct alignas(8 * sizeof(T)) Vec8 { T e[8]; };
+    *reinterpret_cast<Vec8 *>(dk + k_index(p.kv_layout, page, p.Hkv, kvh, slot, g * 8, p.d)) = *reinterpret_cast<const Vec8 *>(sk);
+    if (p.kv_layout == SPEC_KV_TOKEN_MAJOR) {
+        *reinterpret_cast<Vec8 *>(dv + v_index(p.kv_layout, page, p.Hkv, kvh, slot, g * 8, p.d)) = *reinterpret_cast<const Vec8 *>(sv);
+    } else {
+        const Vec8 v = *reinterpret_cast<const Vec8 *>(sv);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const int c = g * 8 + e;
-        dk[k_index(p.kv_layout, page, p.Hkv, kvh, slot, c, p.d)] = sk[e];
-        dv[v_index(p.kv_layout, page, p.Hkv, kvh, slot, c, p.d)] = sv[e];
+        for (int e = 0; e < 8; ++e) dv[v_index(p.kv_layout, page, p.Hkv, kvh, slot, g * 8 + e, p.d)] = v.e[e];
     }
 }
 

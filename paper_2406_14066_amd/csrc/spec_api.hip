@@ -825,6 +825,10 @@ spec_status spec_kv_append(const spec_kv_append_args *a, void *hip_stream)
         return SPEC_EINVAL;
     if (a->dtype != SPEC_F32 && a->dtype != SPEC_BF16) return SPEC_EINVAL;
     if (a->kv_layout != SPEC_KV_TOKEN_MAJOR && a->kv_layout != SPEC_KV_MFMA) return SPEC_EINVAL;
+    // (rows and pools are moved as vectors of 8 elements)
+    if (((reinterpret_cast<uintptr_t>(a->new_k) | reinterpret_cast<uintptr_t>(a->new_v) |
+          reinterpret_cast<uintptr_t>(a->k_cache) | reinterpret_cast<uintptr_t>(a->v_cache)) & 31) != 0)
+        return SPEC_EINVAL;
     if (a->d != 64 && a->d != 128) return SPEC_EUNSUPPORTED;
     if (a->kv_layout == SPEC_KV_MFMA && a->dtype != SPEC_BF16) return SPEC_EUNSUPPORTED;
     if (a->host_cu_q_len[0] != 0 || a->host_cu_q_len[a->B] != a->T) return SPEC_EINVAL;
