@@ -34,6 +34,11 @@
  *   - Same inputs and same (philox_seed, philox_step) give the same outputs.
  *   - Limits: k_b <= SPEC_K_MAX, block_size == 16, d in {64, 128},
  *     Hq % Hkv == 0, Hq/Hkv <= 16, kv_len[b] >= q_len[b] >= 1.
+ *   - Speed: bf16 with pages in the SPEC_KV_MFMA layout and d == 128 runs on the
+ *     matrix-instruction kernel, the whole step in one launch, for every draft
+ *     length and group width within the limits (up to 9 * 16 fused rows per KV
+ *     head).  fp32, token-major pages and d == 64 run on plain, untuned kernels
+ *     (three launches).  spec_verify_plan tells which path a call takes.
  */
 #ifndef SPEC_VERIFY_H
 #define SPEC_VERIFY_H
@@ -304,26 +309,6 @@ spec_status spec_kv_repack_mfma(const void *src_k, const void *src_v, void *dst_
                                 int32_t num_blocks, int32_t Hkv, int32_t d, void *hip_stream);
 
 /*
- * Measurement aid (not part of the step): per-kernel GPU time from HIP events.
- * Between spec_profile_begin and spec_profile_end every kernel the library
- * launches (up to max_launches of them) gets a pair of events: the step kernel
- * carries them itself (they receive the time stamps of the launch's own begin
- * and end), the other kernels are bracketed by two event records on the launch
- * stream.  spec_profile_end waits for those events and returns, per kernel id,
- * the summed duration in milliseconds and the number of launches (both arrays
- * have SPEC_NUM_KERNELS entries).  begin creates the events, so it must not be
- * called during stream capture; the pair is not thread safe.
- */
-#define SPEC_NUM_KERNELS 5
-#define SPEC_KERNEL_STEP 0          /* the whole step in one launch (attention + rejection sampling) */
-#define SPEC_KERNEL_ATTN 1          /* attention-only launch of the matrix-instruction kernel */
-#define SPEC_KERNEL_ATTN_GENERIC 2  /* generic attention over one KV chunk (fp32 / token-major path) */
-#define SPEC_KERNEL_ATTN_COMBINE 3  /* merge of the generic kernel's chunk partials */
-#define SPEC_KERNEL_REJECT 4        /* rejection-sampling-only launch */
-spec_status spec_profile_begin(int32_t max_launches);
-spec_status spec_profile_end(float *total_ms, int32_t *launches);
-
-/*
  * Host-side speculation control (Section 4.1, "Using Goodput for Speculation"; no GPU
  * work, no device pointers; all pointers are HOST pointers owned by the caller).
  *
@@ -390,6 +375,26 @@ typedef struct {
     int64_t free_kv_tokens;         /* < 0: unlimited */
 } spec_goodput_args;
 int32_t spec_argmax_goodput(const spec_goodput_args *args, double *goodput_per_k);
+
+/*
+ * Measurement aid (not part of the step): per-kernel GPU time from HIP events.
+ * Between spec_profile_begin and spec_profile_end every kernel the library
+ * launches (up to max_launches of them) gets a pair of events: the step kernel
+ * carries them itself (they receive the time stamps of the launch's own begin
+ * and end), the other kernels are bracketed by two event records on the launch
+ * stream.  spec_profile_end waits for those events and returns, per kernel id,
+ * the summed duration in milliseconds and the number of launches (both arrays
+ * have SPEC_NUM_KERNELS entries).  begin creates the events, so it must not be
+ * called during stream capture; the pair is not thread safe.
+ */
+#define SPEC_NUM_KERNELS 5
+#define SPEC_KERNEL_STEP 0          /* the whole step in one launch (attention + rejection sampling) */
+#define SPEC_KERNEL_ATTN 1          /* attention-only launch of the matrix-instruction kernel */
+#define SPEC_KERNEL_ATTN_GENERIC 2  /* generic attention over one KV chunk (fp32 / token-major path) */
+#define SPEC_KERNEL_ATTN_COMBINE 3  /* merge of the generic kernel's chunk partials */
+#define SPEC_KERNEL_REJECT 4        /* rejection-sampling-only launch */
+spec_status spec_profile_begin(int32_t max_launches);
+spec_status spec_profile_end(float *total_ms, int32_t *launches);
 
 const char *spec_status_string(spec_status status);
 
