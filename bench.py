@@ -87,14 +87,14 @@ def describe(w):
             % (w.name, w.B, _span(w.kv_len), _span(w.k), w.Hq, w.Hkv, w.d, kv, w.V))
 
 
-def measure(w, args, mode, with_graph):
+def measure(w, args, mode, with_graph, token_major=False):
     """Times K steps of workload w: wall clock without events, kernel time with events attached."""
     import torch
     from paper_2406_14066_amd import spec_verify as sv
     from paper_2406_14066_amd.harness import DeviceStep
 
     # bf16 workloads keep their pages in the matrix-operand layout; the tiny fp32 one (c1) has token-major pages
-    layout = sv.KV_MFMA if w.dtype == "bf16" else sv.KV_TOKEN_MAJOR
+    layout = sv.KV_MFMA if (w.dtype == "bf16" and not token_major) else sv.KV_TOKEN_MAJOR
     ds = DeviceStep(w, kv_layout=layout, with_debug=False, accept_mode=mode)
     plan = ds.plan()
     attn_bytes = w.attn_algorithmic_bytes()
@@ -230,6 +230,7 @@ def brief(mm, traffic):
         "frac": mm["achieved"] / HBM_PEAK_GBS,
         "traffic": traffic,
         "attention_path": {1: "matrix instructions", 2: "generic"}[mm["plan"]["attn_path"]],
+        "kv_layout": "token-major pages" if mm["ds"].kv_layout == 0 else "matrix-operand tiles",
         "row_tiles": mm["plan"]["row_tiles"], "row_groups": mm["plan"]["row_groups"],
         "chunk_tokens": mm["plan"]["chunk_tokens"], "launches": mm["plan"]["launches"],
         "early_stop": mm["plan"]["early_stop"],
@@ -265,10 +266,21 @@ def main():
             wo = make_workload(name, **kw)
             mo = measure(wo, args, mode, with_graph=False)
             others[name] = brief(mo, traffic_from_profile(name) if mode == sv.ACCEPT_SAMPLE else None)
-            del mo, wo
+            del mo
             torch.cuda.empty_cache()
+            if name == "c2":   # the same step on token-major pages (V transposed through LDS inside the kernel)
+                mo = measure(wo, args, mode, with_graph=False, token_major=True)
+                others[name + "_token_major_pages"] = brief(mo, None)
+                del mo
+                torch.cuda.empty_cache()
+            del wo
 
     w = make_workload(args.workload, args.k, args.alpha)
+    if not args.only and w.dtype == "bf16" and w.Hq // w.Hkv * int(w.q_len.max()) <= 48:
+        mo = measure(w, args, mode, with_graph=False, token_major=True)
+        others[w.name + "_token_major_pages"] = brief(mo, None)
+        del mo
+        torch.cuda.empty_cache()
     mm = measure(w, args, mode, with_graph=not args.no_graph)
     res = mm["res"]
     sec_per_step = mm["sec_per_step"]

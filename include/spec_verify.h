@@ -34,11 +34,13 @@
  *   - Same inputs and same (philox_seed, philox_step) give the same outputs.
  *   - Limits: k_b <= SPEC_K_MAX, block_size == 16, d in {64, 128},
  *     Hq % Hkv == 0, Hq/Hkv <= 16, kv_len[b] >= q_len[b] >= 1.
- *   - Speed: bf16 with pages in the SPEC_KV_MFMA layout and d == 128 runs on the
- *     matrix-instruction kernel, the whole step in one launch, for every draft
+ *   - Speed: bf16 with d == 128 runs on the matrix-instruction kernel, the whole
+ *     step in one launch: with pages in the SPEC_KV_MFMA layout for every draft
  *     length and group width within the limits (up to 9 * 16 fused rows per KV
- *     head).  fp32, token-major pages and d == 64 run on plain, untuned kernels
- *     (three launches).  spec_verify_plan tells which path a call takes.
+ *     head), with token-major pages up to 48 fused rows (3 to 8% slower: V is
+ *     transposed through LDS inside the kernel).  fp32, d == 64 and wider
+ *     token-major shapes run on plain, untuned kernels (three launches).
+ *     spec_verify_plan tells which path a call takes.
  */
 #ifndef SPEC_VERIFY_H
 #define SPEC_VERIFY_H

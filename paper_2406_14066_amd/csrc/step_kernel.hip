@@ -58,6 +58,8 @@
 #include <stddef.h>
 #include <string.h>
 
+#include <type_traits>
+
 namespace specv {
 
 namespace {
@@ -970,7 +972,17 @@ constexpr int kOStride = kD * 4 + 16;   // bytes per fp32 output row in LDS
 // rows) the groups of one block read the same pages at the same time, so the pages cross the
 // memory interface once and the groups find each other's loads in the compute unit's cache or
 // in flight.
-template <int NT, int WG>
+// Token-major pages ([16 tokens][128 dims] per page and KV head).  K is loaded straight into the
+// matrix operand order from that layout too (a lane's 16 bytes are 8 consecutive dims of one
+// token); V has to be transposed (the PV product wants, per lane, four consecutive tokens of one
+// dim): each wavefront loads its V page as whole rows (coalesced 16-byte loads), stages it in a
+// region of its own in LDS and reads it back two bytes at a time in operand order.  Token rows
+// are padded to 272 bytes: the 16 lanes of a row group then read 8 banks, and the four row groups
+// of a wavefront, 4 tokens apart, land 16 banks apart: no conflicts.
+constexpr int kVtRowBytes = kD * 2 + 16;
+constexpr int kVtWaveBytes = SPEC_BLOCK_SIZE * kVtRowBytes;
+
+template <int NT, int WG, bool TM = false>
 struct AttnShared {
     static constexpr int kRowsMax = WG * NT * 16;
     union {
@@ -981,6 +993,7 @@ struct AttnShared {
     float m[2][NT][kWave];
     float l[2][NT][kWave];
     int last;
+    alignas(16) unsigned char vt[TM ? kWaves * kVtWaveBytes : 16];   // token-major pages: V staged per wavefront
 };
 
 // The order in which the attention items take the requests (longest first), as the kernel
@@ -993,9 +1006,14 @@ struct OrderTable {
     uniform_u32_ptr pairs;
 };
 
-template <int NT, int WG, bool SPLIT_P>
-__device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order, int item, AttnShared<NT, WG> &sh)
+// VAR: 0 = pages in the matrix-operand layout, softmax weights fed as bf16 high + low parts;
+//      1 = the same with the weights as one bf16 (an experiment switch);
+//      2 = token-major pages (V transposed through LDS), weights as high + low parts.
+template <int NT, int WG, int VAR>
+__device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order, int item, AttnShared<NT, WG, VAR == 2> &sh)
 {
+    constexpr bool SPLIT_P = VAR != 1;
+    constexpr bool TM = VAR == 2;
     constexpr int PW = kWaves / WG;   // wavefronts that share the pages of a group between them
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -1109,8 +1127,16 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
             const_cast<char *>(khead + (size_t)page * page_stride), 0, bytes, kBufferFlags);
         const __amdgpu_buffer_rsrc_t vd = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<char *>(vhead + (size_t)page * page_stride), 0, bytes, kBufferFlags);
+        if constexpr (TM) {
+            // K: token n16, dims 32 i + 8 g .. + 7 sit at n16 * 256 + 64 i + 16 g
 #pragma unroll
-        for (int i = 0; i < 4; ++i) r.k[i] = __builtin_amdgcn_raw_buffer_load_b128(kd, lane_off, i * 1024, kStreamPolicy);
+            for (int i = 0; i < 4; ++i)
+                r.k[i] = __builtin_amdgcn_raw_buffer_load_b128(kd, n16 * (kD * 2) + g * 16, i * 64, kStreamPolicy);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) r.k[i] = __builtin_amdgcn_raw_buffer_load_b128(kd, lane_off, i * 1024, kStreamPolicy);
+        }
+        // V: in operand order already, or (token-major) as whole rows: lane L holds token 4 i + L / 16, dims 8 (L % 16) .. + 7
 #pragma unroll
         for (int i = 0; i < 4; ++i) r.v[i] = __builtin_amdgcn_raw_buffer_load_b128(vd, lane_off, i * 1024, kStreamPolicy);
     };
@@ -1133,6 +1159,34 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
         const int page_tok = tok0 + pi * SPEC_BLOCK_SIZE;
         const bool need_mask = page_tok + SPEC_BLOCK_SIZE > first_masked_token;
         const int tbase = page_tok + 4 * g;
+
+        if constexpr (TM) {
+            // V through this wavefront's LDS region: rows in, operand order out (LDS executes a
+            // wavefront's accesses in order, so the reads see the writes without a barrier)
+            unsigned char *vl = sh.vt + wave * kVtWaveBytes;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                *reinterpret_cast<u32x4 *>(vl + (4 * i + (lane >> 4)) * kVtRowBytes + (lane & 15) * 16) = cur.v[i];
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            const unsigned char *src = vl + (4 * g) * kVtRowBytes + n16 * 2;
+#pragma unroll
+            for (int pp = 0; pp < 4; ++pp) {
+                uint32_t w[4];
+#pragma unroll
+                for (int hf = 0; hf < 2; ++hf) {
+                    const unsigned char *e = src + (32 * pp + 16 * hf) * 2;
+                    const uint32_t t0 = *reinterpret_cast<const uint16_t *>(e);
+                    const uint32_t t1 = *reinterpret_cast<const uint16_t *>(e + kVtRowBytes);
+                    const uint32_t t2 = *reinterpret_cast<const uint16_t *>(e + 2 * kVtRowBytes);
+                    const uint32_t t3 = *reinterpret_cast<const uint16_t *>(e + 3 * kVtRowBytes);
+                    w[2 * hf + 0] = t0 | (t1 << 16);
+                    w[2 * hf + 1] = t2 | (t3 << 16);
+                }
+                cur.v[pp] = (u32x4){w[0], w[1], w[2], w[3]};
+            }
+        }
 
         if (page_tok + SPEC_BLOCK_SIZE > L) {
             // slots past kv_len in the request's last page may hold anything: clear their V
@@ -1456,7 +1510,7 @@ struct StepArgs {
     UnitOrder order;
 };
 
-template <int NT, int WG, bool HAS_ATTN, bool HAS_REJECT, bool SPLIT_P>
+template <int NT, int WG, bool HAS_ATTN, bool HAS_REJECT, int VAR>
 __global__ __launch_bounds__(kThreads, 2) void spec_step_kernel(StepArgs args)
 {
     const AttnParams &ap = args.ap;
@@ -1519,12 +1573,12 @@ __global__ __launch_bounds__(kThreads, 2) void spec_step_kernel(StepArgs args)
         }
     }
     if constexpr (HAS_ATTN) {
-        __shared__ AttnShared<NT, WG> ash;
+        __shared__ AttnShared<NT, WG, VAR == 2> ash;
         OrderTable order;
         order.n = args.order.n;
         order.pairs = (uniform_u32_ptr)((const char __attribute__((address_space(4))) *)__builtin_amdgcn_kernarg_segment_ptr() +
                                         offsetof(StepArgs, order) + offsetof(UnitOrder, request));
-        attn_role<NT, WG, SPLIT_P>(ap, order, item, ash);
+        attn_role<NT, WG, VAR>(ap, order, item, ash);
     }
 }
 
@@ -1565,23 +1619,21 @@ hipError_t launch(const AttnParams &ap, const RejectParams &rp, int n_stat, int 
     const dim3 grid(mixed ? (rows_attn_all + rows_reject) * kXcds
                           : (HAS_ATTN && HAS_REJECT ? (rows_attn_all + rows_reject) * kXcds : n_reject + n_attn));
     // (with events the extended launch attaches them to the kernel's own begin and end)
-    // The variant that feeds the softmax weights as one bf16 (an experiment switch) exists for one wave group only.
-    if constexpr (WG == 1) {
-        if (HAS_ATTN && !ap.split_p) {
-            if (ev.start != nullptr)
-                hipExtLaunchKernelGGL((spec_step_kernel<NT, WG, HAS_ATTN, HAS_REJECT, false>), grid, dim3(kThreads), 0, stream,
-                                      ev.start, ev.stop, 0, args);
-            else
-                hipLaunchKernelGGL((spec_step_kernel<NT, WG, HAS_ATTN, HAS_REJECT, false>), grid, dim3(kThreads), 0, stream, args);
-            return hipGetLastError();
-        }
+    auto go = [&](auto var) {
+        constexpr int VAR = decltype(var)::value;
+        if (ev.start != nullptr)
+            hipExtLaunchKernelGGL((spec_step_kernel<NT, WG, HAS_ATTN, HAS_REJECT, VAR>), grid, dim3(kThreads), 0, stream, ev.start,
+                                  ev.stop, 0, args);
+        else
+            hipLaunchKernelGGL((spec_step_kernel<NT, WG, HAS_ATTN, HAS_REJECT, VAR>), grid, dim3(kThreads), 0, stream, args);
+        return hipGetLastError();
+    };
+    // Token-major pages and the single-bf16 experiment exist for one wave group only.
+    if constexpr (WG == 1 && HAS_ATTN) {
+        if (ap.kv_layout == SPEC_KV_TOKEN_MAJOR) return go(std::integral_constant<int, 2>());
+        if (!ap.split_p) return go(std::integral_constant<int, 1>());
     }
-    if (ev.start != nullptr)
-        hipExtLaunchKernelGGL((spec_step_kernel<NT, WG, HAS_ATTN, HAS_REJECT, true>), grid, dim3(kThreads), 0, stream,
-                              ev.start, ev.stop, 0, args);
-    else
-        hipLaunchKernelGGL((spec_step_kernel<NT, WG, HAS_ATTN, HAS_REJECT, true>), grid, dim3(kThreads), 0, stream, args);
-    return hipGetLastError();
+    return go(std::integral_constant<int, 0>());
 }
 
 }  // namespace
@@ -1609,7 +1661,8 @@ hipError_t launch_step_fused(const AttnParams *attn, int row_tiles, const Reject
         ap = *attn;
         // tiles per wave group and wave groups per block that the kernel is built for
         const bool shape_ok = (ap.row_groups == 1 && row_tiles >= 1 && row_tiles <= 3) ||
-                              ((ap.row_groups == 2 || ap.row_groups == 4) && (row_tiles == 2 || row_tiles == 3));
+                              ((ap.row_groups == 2 || ap.row_groups == 4) && (row_tiles == 2 || row_tiles == 3) &&
+                               ap.kv_layout == SPEC_KV_MFMA);
         // (a wavefront keeps the block-table entries of its pages one per lane)
         if (ap.d != kD || !shape_ok || ap.chunk_tokens > 4096 / ap.row_groups || ap.chunk_tokens % SPEC_BLOCK_SIZE != 0 ||
             ap.capacity_tokens > ap.chunk_tokens * ap.max_chunks ||

@@ -170,6 +170,26 @@ def test_whole_step_with_early_stop(harness, tuning):
     check_reject(w, res)
 
 
+@pytest.mark.parametrize("name,kw,tiles", [("c2", dict(B=4, L_scale=0.5), 1), ("c4", dict(B=32, L_scale=0.5, V=4096), 2),
+                                           ("c5", dict(L_scale=0.1, V=8192), 3)], ids=["c2_small", "c4_small", "c5_small"])
+def test_token_major_pages_on_the_matrix_path(harness, name, kw, tiles):
+    """bf16 token-major pages ([16 tokens][128 dims]): K loaded straight into operand order, V transposed
+    through LDS; the whole step in one launch, one, two and three row tiles."""
+    print("case token-major matrix path", name, flush=True)
+    w = W.config(name, **kw)
+    ds = harness.DeviceStep(w, kv_layout=sv.KV_TOKEN_MAJOR)
+    plan = ds.plan()
+    assert plan["attn_path"] == sv.PATH_MFMA and plan["row_tiles"] == tiles and plan["launches"] == 1, plan
+    ds.run_step()
+    res = ds.results()
+    err = check_attn(w, res["out"])
+    check_reject(w, res)
+    ds.out.fill_(float("nan"))
+    ds.run_attn()
+    check_attn(w, ds.results()["out"])
+    print("%s token-major: attn err %.2e" % (name, err))
+
+
 def test_counters_accumulate_and_runs_are_deterministic(harness):
     print("case determinism", flush=True)
     w = W.config("c2", B=2, L_scale=0.25)

@@ -232,10 +232,10 @@ def test_static_scratch_entry_refuses_what_does_not_fit():
     library's scratch array is refused before anything touches the GPU, and argument errors come
     back as from spec_verify_step."""
     L = sv.lib()
-    # token-major pages take the generic kernel: one partial per (row, head, 256-token chunk)
+    # fp32 takes the generic kernel: one partial per (row, head, 256-token chunk)
     q_len = (9,) * 12
     a = _attn(B=12, Hq=32, Hkv=8, d=128, kv_len=(8000,) * 12, q_len=q_len, max_blocks=500,
-              dtype=sv.SPEC_BF16, layout=sv.KV_TOKEN_MAJOR)
+              dtype=sv.SPEC_F32, layout=sv.KV_TOKEN_MAJOR)
     r = _reject(B=12, V=32, q_len=q_len)
     assert sv.spec_verify_workspace_bytes(a, r) > sv.STATIC_SCRATCH_BYTES
     assert L.spec_verify_step_static(C.byref(a), C.byref(r), None) == sv.SPEC_EWORKSPACE
@@ -335,9 +335,13 @@ def test_every_supported_row_count_takes_the_matrix_path(Hq, Hkv, k, path, tiles
     info = sv.spec_verify_plan(a, None)
     assert (info["attn_path"], info["row_tiles"], info["row_groups"]) == (path, tiles, groups), info
     assert info["launches"] == 1
-    # the other page layout, fp32 and d = 64 take the generic kernels
+    # token-major bf16 pages stay on the matrix path up to 48 fused rows (V transposed through LDS), beyond
+    # that, like fp32 and d = 64, they take the generic kernels
+    tm = sv.spec_verify_plan(_attn(B=B, Hq=Hq, Hkv=Hkv, kv_len=(300,) * B, q_len=(k + 1,) * B, max_blocks=32,
+                                   layout=sv.KV_TOKEN_MAJOR), None)
+    assert tm["attn_path"] == (sv.PATH_MFMA if groups == 1 else sv.PATH_GENERIC), tm
     assert sv.spec_verify_plan(_attn(B=B, Hq=Hq, Hkv=Hkv, kv_len=(300,) * B, q_len=(k + 1,) * B, max_blocks=32,
-                                     layout=sv.KV_TOKEN_MAJOR), None)["attn_path"] == sv.PATH_GENERIC
+                                     dtype=sv.SPEC_F32, layout=sv.KV_TOKEN_MAJOR), None)["attn_path"] == sv.PATH_GENERIC
     assert sv.spec_verify_plan(_attn(B=B, Hq=Hq, Hkv=Hkv, d=64, kv_len=(300,) * B, q_len=(k + 1,) * B,
                                      max_blocks=32), None)["attn_path"] == sv.PATH_GENERIC
 
