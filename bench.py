@@ -205,7 +205,7 @@ def measure(w, args, mode, with_graph, token_major=False):
     step_us = sum(kernel_us[k] or 0.0 for k in ("step", "attn_generic", "attn_combine", "reject"))
     achieved = step_bytes / (step_us * 1e-6) / 1e9
     out = dict(
-        w=w, ds=ds, res=res, plan=plan, nrot=nrot, sec_per_step=sec_per_step, sec_per_step_events=sec_per_step_events,
+        w=w, ds=ds, layout=layout, res=res, plan=plan, nrot=nrot, sec_per_step=sec_per_step, sec_per_step_events=sec_per_step_events,
         host_us_per_call=(t_enqueued - t0) / args.steps * 1e6, kernel_us=kernel_us, step_us=step_us, achieved=achieved,
         attn_bytes=attn_bytes, rej_bytes=rej_bytes, step_bytes=step_bytes, rej_bytes_needed=rej_bytes_needed,
         emitted_per_step=emitted_per_step, graph_info=graph_info, events_in_region=events_in_region,
@@ -230,7 +230,7 @@ def brief(mm, traffic):
         "frac": mm["achieved"] / HBM_PEAK_GBS,
         "traffic": traffic,
         "attention_path": {1: "matrix instructions", 2: "generic"}[mm["plan"]["attn_path"]],
-        "kv_layout": "token-major pages" if mm["ds"].kv_layout == 0 else "matrix-operand tiles",
+        "kv_layout": "token-major pages" if mm["layout"] == 0 else "matrix-operand tiles",
         "row_tiles": mm["plan"]["row_tiles"], "row_groups": mm["plan"]["row_groups"],
         "chunk_tokens": mm["plan"]["chunk_tokens"], "launches": mm["plan"]["launches"],
         "early_stop": mm["plan"]["early_stop"],
@@ -257,9 +257,19 @@ def main():
 
     mode = {"sample": sv.ACCEPT_SAMPLE, "greedy": sv.ACCEPT_GREEDY, "point": sv.ACCEPT_POINT_DRAFT}[args.accept_mode]
 
-    # the other workloads first (each frees its device memory before the next), the headline one last
+    # the headline workload first, on a fresh device; then the others (each frees its device memory before the next)
+    w = make_workload(args.workload, args.k, args.alpha)
+    mm = measure(w, args, mode, with_graph=not args.no_graph)
+    del mm["ds"]      # (frees the headline workload's device memory)
+    torch.cuda.empty_cache()
     others = {}
     if not args.only:
+        if w.dtype == "bf16" and w.Hq // w.Hkv * int(w.q_len.max()) <= 48:
+            # the same step on token-major pages (V transposed through LDS inside the kernel)
+            mo = measure(w, args, mode, with_graph=False, token_major=True)
+            others[w.name + "_token_major_pages"] = brief(mo, None)
+            del mo
+            torch.cuda.empty_cache()
         for name, kw in [("c1", {}), ("c2", {}), ("c3", dict(k=4, alpha=0.7)), ("c5", {}), ("c4_k7", {})]:
             if name == args.workload:
                 continue
@@ -268,20 +278,12 @@ def main():
             others[name] = brief(mo, traffic_from_profile(name) if mode == sv.ACCEPT_SAMPLE else None)
             del mo
             torch.cuda.empty_cache()
-            if name == "c2":   # the same step on token-major pages (V transposed through LDS inside the kernel)
+            if name == "c2":
                 mo = measure(wo, args, mode, with_graph=False, token_major=True)
                 others[name + "_token_major_pages"] = brief(mo, None)
                 del mo
                 torch.cuda.empty_cache()
             del wo
-
-    w = make_workload(args.workload, args.k, args.alpha)
-    if not args.only and w.dtype == "bf16" and w.Hq // w.Hkv * int(w.q_len.max()) <= 48:
-        mo = measure(w, args, mode, with_graph=False, token_major=True)
-        others[w.name + "_token_major_pages"] = brief(mo, None)
-        del mo
-        torch.cuda.empty_cache()
-    mm = measure(w, args, mode, with_graph=not args.no_graph)
     res = mm["res"]
     sec_per_step = mm["sec_per_step"]
     traffic = traffic_from_profile(args.workload) if mode == sv.ACCEPT_SAMPLE else None
