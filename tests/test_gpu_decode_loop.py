@@ -24,9 +24,10 @@ def _bf16_dev(a, dev):
     (8, 2, 3, [60, 125, 250, 700, 1000, 62]),          # 16 rows per KV head: one wave group
     (32, 2, 4, [63, 1279, 15, 640]),                   # 80 rows per KV head: two wave groups per block
 ], ids=["gqa4_k3", "gqa16_k4_row_groups"])
-def test_captured_step_survives_a_decode_loop(Hq, Hkv, k, start):
+def test_captured_step_survives_a_decode_loop(Hq, Hkv, k, start, tuning):
     import torch
     dev = "cuda"
+    tuning("SPEC_VERIFY_CHUNK", 64)   # short chunks, so that the growing requests cross chunk boundaries within a few steps
     B, d, V = len(start), 128, 4096
     q_len = np.full(B, k + 1, dtype=np.int32)
     cu = np.concatenate([[0], np.cumsum(q_len)]).astype(np.int32)

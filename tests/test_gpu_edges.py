@@ -121,16 +121,16 @@ def test_workspace_reused_across_shapes(harness):
             check_reject(w, res)
 
 
-@pytest.mark.parametrize("kw,chunk", [
-    (dict(B=1, Hq=4, Hkv=1, d=128, kv_len=[8197], k=[3]), None),             # one unit split into more than 64 chunks by the planner
-    (dict(B=2, Hq=8, Hkv=2, d=128, kv_len=[4500, 300], k=[2, 5]), 64),       # ... and by the chunk-size switch, beside an unsplit request
-], ids=["planner", "switch"])
-def test_more_than_64_chunks_take_the_separate_merge_launch(harness, tuning, kw, chunk):
+@pytest.mark.parametrize("kw,switch,value", [
+    (dict(B=1, Hq=4, Hkv=1, d=128, kv_len=[8197], k=[3]), "SPEC_VERIFY_TARGET_BLOCKS", 256),   # one unit cut into a block per compute unit
+    (dict(B=2, Hq=8, Hkv=2, d=128, kv_len=[4500, 300], k=[2, 5]), "SPEC_VERIFY_CHUNK", 64),    # short chunks, beside an unsplit request
+], ids=["block_target", "chunk_size"])
+def test_more_than_64_chunks_take_the_separate_merge_launch(harness, tuning, kw, switch, value):
     """The matrix kernel's last-arriver merge handles up to 64 chunks per request; beyond that the
-    partials are merged by a launch of their own."""
-    print("case many chunks", kw["kv_len"], chunk, flush=True)
-    if chunk:
-        tuning("SPEC_VERIFY_CHUNK", chunk)
+    partials are merged by a launch of their own.  (The planner itself gets there only beyond
+    64 x 4096 tokens in one request; the tuning switches force it at a size the oracle can check.)"""
+    print("case many chunks", kw["kv_len"], switch, value, flush=True)
+    tuning(switch, value)
     w = W.make_workload("chunks", V=64, dtype="bf16", draft_std=2.0, sigma=1.0, data_seed=31, philox_seed=8, **kw)
     ds = harness.DeviceStep(w, kv_layout=sv.KV_MFMA)
     plan = ds.plan()
