@@ -496,7 +496,11 @@ __device__ __forceinline__ bool wait_all(int spin_limit, F probe)
 {
     for (int spin = 0; spin < spin_limit; ++spin) {
         if (__syncthreads_and(probe() ? 1 : 0)) return true;
-        __builtin_amdgcn_s_sleep(32);
+        // (short naps first: in a small launch the data is a poll or two away and a long nap would be
+        // most of the wait; in a large one the waiting blocks must not crowd the memory system)
+        if (spin < 4) __builtin_amdgcn_s_sleep(2);
+        else if (spin < 8) __builtin_amdgcn_s_sleep(8);
+        else __builtin_amdgcn_s_sleep(32);
     }
     return false;
 }
