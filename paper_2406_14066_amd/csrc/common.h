@@ -36,6 +36,7 @@ struct AttnPlan {
     int32_t row_groups;    // wave groups per attention block (1, 2 or 4): row_groups * row_tiles tiles cover max_q_len * (Hq/Hkv) rows
     int32_t capacity_tokens;  // longest kv_len the plan allows for (chunk_tokens * max_chunks, capped by the bucket)
     int32_t fused_combine; // mfma kernel merges the chunk partials itself (few chunks) or leaves it to the combine kernel
+    int32_t short_attn;    // the attention half streams for less time than the rejection stages' chain takes
     size_t acc_bytes;
     size_t ml_bytes;
     size_t ticket_bytes;
@@ -59,7 +60,7 @@ struct AttnParams {
     int32_t reject_even_limit;    // ... when there are at most this many attention blocks (the number of compute units)
     int32_t capacity_tokens;      // a request whose device-side kv_len exceeds this is skipped and counted in *errors
     int32_t row_groups;           // see AttnPlan
-    int32_t reserved;
+    int32_t reject_first_limit;   // fused step: up to this many rejection items go first in the grid (0: never)
     const void *q, *k_cache, *v_cache;
     const int32_t *block_table, *kv_len, *cu_q_len;
     float *out;

@@ -101,6 +101,7 @@ struct Tuning {
     int early_stop = -1;          // SPEC_VERIFY_EARLY_STOP=0/1: statistics in position order (-1: automatic)
     float reject_span = 0.5f;     // SPEC_VERIFY_REJECT_SPAN: fraction of the attention items among which the rejection items are spread
     long attn_first_limit = -1;   // SPEC_VERIFY_ATTN_FIRST_LIMIT: attention blocks up to which they all precede the rejection blocks (-1: automatic)
+    int reject_first_limit = 1024; // SPEC_VERIFY_REJECT_FIRST_LIMIT: rejection blocks up to which they precede the blocks of a short attention half
     int split_p = 1;              // SPEC_VERIFY_SPLIT_P=0: softmax weights as one bf16 instead of high + low parts
     int reject_even = 1;          // SPEC_VERIFY_REJECT_EVEN=0: rejection blocks on all XCDs
     int spin_limit = 1 << 20;     // SPEC_VERIFY_SPIN_LIMIT: polls of a bounded wait (about a second at the default)
@@ -134,6 +135,10 @@ void read_tuning()
     if (const char *e = getenv("SPEC_VERIFY_ATTN_FIRST_LIMIT")) {
         const long v = strtol(e, nullptr, 10);
         if (v >= 0 && v <= (1 << 20)) t.attn_first_limit = v;
+    }
+    if (const char *e = getenv("SPEC_VERIFY_REJECT_FIRST_LIMIT")) {
+        const long v = strtol(e, nullptr, 10);
+        if (v >= 0 && v <= (1 << 20)) t.reject_first_limit = (int)v;
     }
     if (const char *e = getenv("SPEC_VERIFY_SPLIT_P")) t.split_p = e[0] != '0';
     if (const char *e = getenv("SPEC_VERIFY_REJECT_EVEN")) t.reject_even = e[0] != '0';
@@ -564,6 +569,7 @@ const StepPlan &plan_for(const spec_attn_args *a, const spec_reject_args *r)
     size_t base = 0;
     if (a != nullptr) {
         e.apl = plan_attn(a, tu);
+        e.apl.short_attn = attn_estimate_us(a) <= 20.0 ? 1 : 0;
         if (e.apl.use_mfma) make_order(a, e.order);
         base = e.apl.total_bytes;
     }
@@ -616,6 +622,7 @@ AttnParams attn_params(const spec_attn_args *a, const AttnPlan &pl, char *ws, in
     p.attn_first_limit = tu.attn_first_limit >= 0 ? (int32_t)tu.attn_first_limit : 2 * compute_units();
     p.reject_even_xcds = tu.reject_even;
     p.reject_even_limit = compute_units();
+    p.reject_first_limit = pl.short_attn ? tu.reject_first_limit : 0;
     return p;
 }
 
