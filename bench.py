@@ -201,7 +201,8 @@ def measure(w, args, mode, with_graph, token_major=False):
 
     kernel_us = {k: (1e3 * ms / n if n else None) for k, (ms, n) in kt.items()}
     # the step is the one launch of the step kernel (plus a merge launch only when a request has more than 64
-    # chunks); on the generic path (fp32) it is three launches: attention partials, their merge, rejection sampling
+    # chunks); on the generic path (fp32) it is two or three launches: attention, a merge if a request is split,
+    # rejection sampling
     step_us = sum(kernel_us[k] or 0.0 for k in ("step", "attn_generic", "attn_combine", "reject"))
     achieved = step_bytes / (step_us * 1e-6) / 1e9
     out = dict(

@@ -95,7 +95,8 @@ typedef struct {
     int32_t T;                  /* sum_b q_len[b], q_len[b] = k_b + 1 */
     int32_t qkv_dtype;          /* spec_dtype of q, k_cache, v_cache; out is fp32 */
     int32_t kv_layout;          /* spec_kv_layout */
-    const void *q;              /* [T][Hq][d], rows packed by request: rows cu_q_len[b]..cu_q_len[b+1]-1 */
+    const void *q;              /* [T][Hq][d], rows packed by request: rows cu_q_len[b]..cu_q_len[b+1]-1
+                                   (q, k_cache, v_cache and out must be 32-byte aligned: SPEC_EINVAL otherwise) */
     const void *k_cache;        /* page pool, see spec_kv_layout */
     const void *v_cache;
     const int32_t *block_table; /* [B][max_blocks_per_req]; entries past ceil(kv_len/16) are not read */

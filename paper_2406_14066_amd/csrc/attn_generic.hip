@@ -9,7 +9,8 @@
 //                         matrix-instruction kernel does not take.
 //   attn_combine_kernel   merges the per-chunk partial results of either
 //                         attention kernel: out = sum_c w_c acc_c / sum_c w_c l_c,
-//                         w_c = 2^(m_c - max_c m_c).
+//                         w_c = 2^(m_c - max_c m_c).  Requests with one chunk are
+//                         written by the kernel that holds their only partial.
 //   kv_repack_kernel      token-major pages -> matrix-instruction page layout.
 //
 // Scores are kept in base-2 units (the softmax scale is folded with log2 e).
@@ -105,9 +106,17 @@ __global__ __launch_bounds__(kChunkThreads) void attn_generic_kernel(AttnParams 
         page = p.block_table[(size_t)b * p.max_blocks_per_req + token / SPEC_BLOCK_SIZE];
         const int slot = token % SPEC_BLOCK_SIZE;
         if ((unsigned)page < (unsigned)p.num_blocks) {
+            // eight consecutive head dims are contiguous in both page layouts: one vector load per
+            // group, several groups in flight (element by element the loop is a chain of load
+            // latencies: 37 us for 128 keys of 64 dims)
+            struct alignas(8 * sizeof(KV_T)) Vec8 { KV_T e[8]; };
             float dot = 0.0f;
-            for (int c = 0; c < d; ++c)
-                dot = fmaf(sh_q[c], load_as_float(kc, k_index(p.kv_layout, page, p.Hkv, kvh, slot, c, d)), dot);
+#pragma unroll 8
+            for (int c = 0; c < d; c += 8) {
+                const Vec8 kv = *reinterpret_cast<const Vec8 *>(kc + k_index(p.kv_layout, page, p.Hkv, kvh, slot, c, d));
+#pragma unroll
+                for (int e = 0; e < 8; ++e) dot = fmaf(sh_q[c + e], load_as_float(kv.e, e), dot);
+            }
             score = dot * p.scale_log2;
         } else {
             // an entry outside the pool is never turned into an address: the page reads as zeros
@@ -136,19 +145,35 @@ __global__ __launch_bounds__(kChunkThreads) void attn_generic_kernel(AttnParams 
     sum = 0.0f;
     for (int w = 0; w < kChunkThreads / kWave; ++w) sum += sh_red[w];
 
-    // weighted sum of values: one head dim per thread
+    // weighted sum of values: the block's 256 / d thread groups take the keys in turn, one head
+    // dim per thread, and the groups' sums are added through shared memory (d is 64 or 128)
     const size_t slot_index = ((size_t)row * p.Hq + h) * p.max_chunks + chunk;
-    if (tid < d) {
+    const int ngrp = kChunkThreads / d;
+    const int grp = tid / d, c = tid % d;
+    {
         const int ntok = min(p.chunk_tokens, last_visible - chunk * p.chunk_tokens + 1);
         float acc = 0.0f;
-        for (int t = 0; t < ntok; ++t) {
+        // (no branch in the loop, so that the loads of several keys are in flight together: a page
+        // that is not there is read as page 0 with weight 0)
+#pragma unroll 8
+        for (int t = grp; t < ntok; t += ngrp) {
             const int slot = (chunk * p.chunk_tokens + t) % SPEC_BLOCK_SIZE;
-            if (sh_page[t] >= 0)
-                acc = fmaf(sh_p[t], load_as_float(vc, v_index(p.kv_layout, sh_page[t], p.Hkv, kvh, slot, tid, d)), acc);
+            const int pg = sh_page[t];
+            const float v = load_as_float(vc, v_index(p.kv_layout, max(pg, 0), p.Hkv, kvh, slot, c, d));
+            acc = fmaf(pg >= 0 ? sh_p[t] : 0.0f, pg >= 0 ? v : 0.0f, acc);
         }
-        p.ws_acc[slot_index * d + tid] = acc;
+        __syncthreads();     // every thread has read its probabilities: the buffer now carries the groups' sums
+        sh_p[tid] = acc;
+        __syncthreads();
     }
-    if (tid == 0) {
+    if (tid < d) {
+        float acc = 0.0f;
+        for (int gi = 0; gi < ngrp; ++gi) acc += sh_p[gi * d + tid];
+        // the only chunk of its request: the row is complete, no merge needed
+        if (nchunks == 1) p.out[((size_t)row * p.Hq + h) * d + tid] = acc / sum;
+        else p.ws_acc[slot_index * d + tid] = acc;
+    }
+    if (tid == 0 && nchunks > 1) {
         p.ws_ml[slot_index * 2 + 0] = mx;
         p.ws_ml[slot_index * 2 + 1] = sum;
     }
@@ -164,7 +189,7 @@ __global__ void attn_combine_kernel(AttnParams p)
     if (!request_lengths_ok(p.kv_len[b], p.cu_q_len[b + 1] - p.cu_q_len[b], p.capacity_tokens, p.max_blocks_per_req))
         return;   // left out by the partial kernel too
     const int nchunks = (p.kv_len[b] + p.chunk_tokens - 1) / p.chunk_tokens;
-    if (nchunks == 1 && p.single_chunk_direct) return;
+    if (nchunks == 1) return;   // written by the kernel that made the partial results
     const size_t base = ((size_t)row * p.Hq + h) * p.max_chunks;
     float mx = kEmptyMax;
 #pragma unroll 8

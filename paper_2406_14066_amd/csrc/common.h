@@ -55,7 +55,7 @@ struct AttnParams {
     int32_t attn_first_limit;     // attention blocks go first in the grid when there are at most this many
     float reject_span;            // fraction of the attention items among which the rejection items are spread in the grid
     int32_t split_p;              // feed the softmax weights to the PV product as bf16 high + low parts
-    int32_t single_chunk_direct;  // requests with one chunk were written straight to `out`: the combine kernel skips them
+    int32_t reserved;
     int32_t reject_even_xcds;     // fused step: rejection blocks only at even positions of the grid's rows of 8 (see GridSplit)
     int32_t reject_even_limit;    // ... when there are at most this many attention blocks (the number of compute units)
     int32_t capacity_tokens;      // a request whose device-side kv_len exceeds this is skipped and counted in *errors

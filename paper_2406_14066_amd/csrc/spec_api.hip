@@ -182,6 +182,10 @@ spec_status validate_attn_scalars(const spec_attn_args *a)
     if (a->q == nullptr || a->k_cache == nullptr || a->v_cache == nullptr || a->block_table == nullptr ||
         a->kv_len == nullptr || a->cu_q_len == nullptr || a->out == nullptr || a->host_cu_q_len == nullptr)
         return SPEC_EINVAL;
+    // (rows and pages move as vectors of up to 32 bytes)
+    if (((reinterpret_cast<uintptr_t>(a->q) | reinterpret_cast<uintptr_t>(a->k_cache) | reinterpret_cast<uintptr_t>(a->v_cache) |
+          reinterpret_cast<uintptr_t>(a->out)) & 31) != 0)
+        return SPEC_EINVAL;
     if (a->max_kv_len < 0 || (a->max_kv_len == 0 && a->host_kv_len == nullptr)) return SPEC_EINVAL;
     if (a->Hq % a->Hkv != 0) return SPEC_EINVAL;
     if (!(a->softmax_scale >= 0.0f) || isinf(a->softmax_scale)) return SPEC_EINVAL;
@@ -615,7 +619,6 @@ AttnParams attn_params(const spec_attn_args *a, const AttnPlan &pl, char *ws, in
     p.errors = reinterpret_cast<unsigned long long *>(a->error_count != nullptr ? a->error_count : errors);
     p.generation = next_generation();
     p.fused_combine = pl.fused_combine;
-    p.single_chunk_direct = pl.use_mfma;
     p.split_p = tu.split_p;
     p.reject_span = tu.reject_span;
     // as many attention blocks as there are block slots: all start at once
@@ -658,6 +661,7 @@ spec_status run_attn_generic(const AttnParams &p, int dtype, hipStream_t stream)
 {
     hipError_t err = timed(SPEC_KERNEL_ATTN_GENERIC, stream, [&] { return launch_attn_generic(p, dtype, stream); });
     if (err != hipSuccess) return SPEC_EHIP;
+    if (p.max_chunks == 1) return SPEC_OK;   // no request is split: every row was written directly
     err = timed(SPEC_KERNEL_ATTN_COMBINE, stream, [&] { return launch_attn_combine(p, stream); });
     return err == hipSuccess ? SPEC_OK : SPEC_EHIP;
 }
@@ -759,7 +763,7 @@ spec_status spec_verify_plan(const spec_attn_args *attn, const spec_reject_args 
             info->launches = 1 + ((!pl.fused_combine && pl.max_chunks > 1) ? 1 : 0);
         } else {
             info->attn_blocks = pl.max_chunks * attn->Hq * attn->T;
-            info->launches = 2;
+            info->launches = pl.max_chunks > 1 ? 2 : 1;
         }
         info->workspace_bytes += pl.total_bytes;
     }

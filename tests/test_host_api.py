@@ -78,6 +78,8 @@ def test_validate_attn_accepts_good_arguments():
     (lambda a: setattr(a, "T", 6), sv.SPEC_EINVAL),               # != cu_q_len[B]
     (lambda a: setattr(a, "max_blocks_per_req", 2), sv.SPEC_EINVAL),  # 40 tokens need 3 pages
     (lambda a: setattr(a, "softmax_scale", -1.0), sv.SPEC_EINVAL),
+    (lambda a: setattr(a, "k_cache", FAKE + 16), sv.SPEC_EINVAL),     # pools, q and out: 32-byte aligned
+    (lambda a: setattr(a, "out", FAKE + 4), sv.SPEC_EINVAL),
     (lambda a: setattr(a, "qkv_dtype", 5), sv.SPEC_EINVAL),
     (lambda a: setattr(a, "block_size", 32), sv.SPEC_EUNSUPPORTED),
     (lambda a: setattr(a, "d", 96), sv.SPEC_EUNSUPPORTED),
