@@ -53,8 +53,12 @@ __device__ __forceinline__ size_t v_index(int layout, int page, int Hkv, int kvh
 }
 
 // request that owns packed query row `row`: largest b with cu_q_len[b] <= row
-__device__ __forceinline__ int find_request(const int32_t *cu_q_len, int B, int row)
+// (T = cu_q_len[B]; with one draft length for all requests the first guess is right, and its two
+// loads replace a chain of log2 B dependent ones)
+__device__ __forceinline__ int find_request(const int32_t *cu_q_len, int B, int T, int row)
 {
+    const int guess = min((int)(((long long)row * B) / T), B - 1);
+    if (cu_q_len[guess] <= row && row < cu_q_len[guess + 1]) return guess;
     int lo = 0, hi = B - 1;
     while (lo < hi) {
         const int mid = (lo + hi + 1) >> 1;
@@ -70,7 +74,7 @@ __global__ __launch_bounds__(kChunkThreads) void attn_generic_kernel(AttnParams 
     const int chunk = blockIdx.x;
     const int h = blockIdx.y;
     const int row = blockIdx.z;
-    const int b = find_request(p.cu_q_len, p.B, row);
+    const int b = find_request(p.cu_q_len, p.B, p.T, row);
     const int q_len = p.cu_q_len[b + 1] - p.cu_q_len[b];
     const int j = row - p.cu_q_len[b];
     const int L = p.kv_len[b];
@@ -185,7 +189,7 @@ __global__ void attn_combine_kernel(AttnParams p)
     const int row = blockIdx.x / p.Hq;
     const int h = blockIdx.x % p.Hq;
     const int tid = threadIdx.x;
-    const int b = find_request(p.cu_q_len, p.B, row);
+    const int b = find_request(p.cu_q_len, p.B, p.T, row);
     if (!request_lengths_ok(p.kv_len[b], p.cu_q_len[b + 1] - p.cu_q_len[b], p.capacity_tokens, p.max_blocks_per_req))
         return;   // left out by the partial kernel too
     const int nchunks = (p.kv_len[b] + p.chunk_tokens - 1) / p.chunk_tokens;
@@ -232,7 +236,7 @@ __global__ void kv_append_kernel(KvAppendParams p)
     const int g = (int)(idx % groups);
     const int kvh = (int)((idx / groups) % p.Hkv);
     const int row = (int)(idx / ((size_t)groups * p.Hkv));
-    const int b = find_request(p.cu_q_len, p.B, row);
+    const int b = find_request(p.cu_q_len, p.B, p.T, row);
     const int q_len = p.cu_q_len[b + 1] - p.cu_q_len[b];
     const int pos = p.kv_len[b] - q_len + (row - p.cu_q_len[b]);
     // position and page index come from device memory: a row that would land outside the

@@ -195,28 +195,6 @@ __device__ __forceinline__ int uniform_load(const int32_t *base, int index)
     return ((uniform_i32_ptr)(uintptr_t)base)[__builtin_amdgcn_readfirstlane(index)];
 }
 
-// request that owns packed target row `row`: largest b with cu_q_len[b] <= row
-__device__ __forceinline__ int request_of_target_row(const int32_t *cu_q_len, int B, int row)
-{
-    int lo = 0, hi = B - 1;
-    while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (cu_q_len[mid] <= row) lo = mid; else hi = mid - 1;
-    }
-    return lo;
-}
-
-// request that owns packed draft row `row`: largest b with cu_q_len[b] - b <= row
-__device__ __forceinline__ int request_of_draft_row(const int32_t *cu_q_len, int B, int row)
-{
-    int lo = 0, hi = B - 1;
-    while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (cu_q_len[mid] - mid <= row) lo = mid; else hi = mid - 1;
-    }
-    return lo;
-}
-
 // ===========================================================================
 // Rejection half
 // ===========================================================================
