@@ -136,9 +136,11 @@ class ControlLoop:
             self.workspace = sv.alloc_workspace(need, self.device)
         before = self.counters.cpu().numpy().copy()
         start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        append, _keep_append = sv.make_kv_append_args(self.new_k[:T], self.new_v[:T], self.k_cache, self.v_cache,
+                                                      self.block_table, self.kv_len, self.cu_q_len, host_len, host_cu,
+                                                      kv_layout=sv.KV_MFMA, error_count=self.append_errors)
         start.record()
-        sv.spec_kv_append(self.new_k[:T], self.new_v[:T], self.k_cache, self.v_cache, self.block_table, self.kv_len,
-                          self.cu_q_len, host_len, host_cu, kv_layout=sv.KV_MFMA, error_count=self.append_errors)
+        sv.spec_kv_append_args(append)
         sv.spec_verify_step(attn, rej, self.workspace)
         stop.record()
         torch.cuda.synchronize()

@@ -1622,10 +1622,11 @@ hipError_t launch(const AttnParams &ap, const RejectParams &rp, int n_stat, int 
             hipLaunchKernelGGL((spec_step_kernel<NT, WG, HAS_ATTN, HAS_REJECT, VAR>), grid, dim3(kThreads), 0, stream, args);
         return hipGetLastError();
     };
-    // Token-major pages and the single-bf16 experiment exist for one wave group only.
-    if constexpr (WG == 1 && HAS_ATTN) {
+    if constexpr (HAS_ATTN) {
         if (ap.kv_layout == SPEC_KV_TOKEN_MAJOR) return go(std::integral_constant<int, 2>());
-        if (!ap.split_p) return go(std::integral_constant<int, 1>());
+        // (the single-bf16 experiment exists for one wave group only)
+        if constexpr (WG == 1)
+            if (!ap.split_p) return go(std::integral_constant<int, 1>());
     }
     return go(std::integral_constant<int, 0>());
 }
@@ -1655,8 +1656,7 @@ hipError_t launch_step_fused(const AttnParams *attn, int row_tiles, const Reject
         ap = *attn;
         // tiles per wave group and wave groups per block that the kernel is built for
         const bool shape_ok = (ap.row_groups == 1 && row_tiles >= 1 && row_tiles <= 3) ||
-                              ((ap.row_groups == 2 || ap.row_groups == 4) && (row_tiles == 2 || row_tiles == 3) &&
-                               ap.kv_layout == SPEC_KV_MFMA);
+                              ((ap.row_groups == 2 || ap.row_groups == 4) && (row_tiles == 2 || row_tiles == 3));
         // (a wavefront keeps the block-table entries of its pages one per lane)
         if (ap.d != kD || !shape_ok || ap.chunk_tokens > 4096 / ap.row_groups || ap.chunk_tokens % SPEC_BLOCK_SIZE != 0 ||
             ap.capacity_tokens > ap.chunk_tokens * ap.max_chunks ||

@@ -301,9 +301,10 @@ def spec_kv_repack_mfma(src_k, src_v, dst_k, dst_v, stream=None) -> None:
                                      nb, Hkv, d, _stream_handle(stream)), "spec_kv_repack_mfma")
 
 
-def spec_kv_append(new_k, new_v, k_cache, v_cache, block_table, kv_len, cu_q_len, host_kv_len, host_cu_q_len, *,
-                   kv_layout: int = KV_TOKEN_MAJOR, stream=None, error_count=None) -> None:
-    """Writes this step's K/V rows [T,Hkv,d] into the paged caches [nb,Hkv,16,d] in place."""
+def make_kv_append_args(new_k, new_v, k_cache, v_cache, block_table, kv_len, cu_q_len, host_kv_len, host_cu_q_len, *,
+                        kv_layout: int = KV_TOKEN_MAJOR, error_count=None):
+    """The argument struct of `spec_kv_append` for tensors that stay where they are (a decode loop
+    appends from the same buffers every step).  Returns (args, keepalive)."""
     hk, hc = _host_i32(host_kv_len), _host_i32(host_cu_q_len)
     a = KvAppendArgs()
     a.T, a.Hkv, a.d = new_k.shape
@@ -317,10 +318,23 @@ def spec_kv_append(new_k, new_v, k_cache, v_cache, block_table, kv_len, cu_q_len
     a.block_table, a.kv_len, a.cu_q_len = block_table.data_ptr(), kv_len.data_ptr(), cu_q_len.data_ptr()
     a.host_kv_len, a.host_cu_q_len = hk.ctypes.data, hc.ctypes.data
     a.error_count = _dev_ptr(error_count)
+    return a, (hk, hc, new_k, new_v, k_cache, v_cache, block_table, kv_len, cu_q_len, error_count)
+
+
+def spec_kv_append_args(args, stream=None) -> None:
+    """`spec_kv_append` on a struct made by `make_kv_append_args`."""
     fn = lib().spec_kv_append
     fn.restype = C.c_int
     fn.argtypes = [C.c_void_p, C.c_void_p]
-    _check(fn(C.addressof(a), _stream_handle(stream)), "spec_kv_append")
+    _check(fn(C.addressof(args), _stream_handle(stream)), "spec_kv_append")
+
+
+def spec_kv_append(new_k, new_v, k_cache, v_cache, block_table, kv_len, cu_q_len, host_kv_len, host_cu_q_len, *,
+                   kv_layout: int = KV_TOKEN_MAJOR, stream=None, error_count=None) -> None:
+    """Writes this step's K/V rows [T,Hkv,d] into the paged caches [nb,Hkv,16,d] in place."""
+    a, _keep = make_kv_append_args(new_k, new_v, k_cache, v_cache, block_table, kv_len, cu_q_len, host_kv_len,
+                                   host_cu_q_len, kv_layout=kv_layout, error_count=error_count)
+    spec_kv_append_args(a, stream)
 
 
 def spec_profile_begin(max_launches: int) -> None:

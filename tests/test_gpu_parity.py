@@ -60,12 +60,13 @@ ROW_GROUP_CASES = [
 ]
 
 
+@pytest.mark.parametrize("layout", [sv.KV_MFMA, sv.KV_TOKEN_MAJOR], ids=["mfma", "token_major"])
 @pytest.mark.parametrize("name,kw,tiles,groups", ROW_GROUP_CASES, ids=[c[0] for c in ROW_GROUP_CASES])
-def test_many_rows_stay_on_the_matrix_path(harness, name, kw, tiles, groups):
-    print("case row groups", name, flush=True)
+def test_many_rows_stay_on_the_matrix_path(harness, name, kw, tiles, groups, layout):
+    print("case row groups", name, "layout", layout, flush=True)
     w = W.make_workload(name, V=64, dtype="bf16", draft_std=2.0, sigma=1.0, data_seed=zlib.crc32(name.encode()) % 1000,
                         philox_seed=3, **kw)
-    ds = harness.DeviceStep(w, kv_layout=sv.KV_MFMA)
+    ds = harness.DeviceStep(w, kv_layout=layout)
     plan = ds.plan()
     assert plan["attn_path"] == sv.PATH_MFMA and plan["row_tiles"] == tiles and plan["row_groups"] == groups, plan
     ds.run_attn()
