@@ -66,8 +66,7 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
-constexpr int kD = 128;
-constexpr int kPageHeadBytes = SPEC_BLOCK_SIZE * kD * 2;  // 4096
+constexpr int kD = 128;   // head dim of the main variants (one for 64 exists for pages in the matrix-operand layout)
 constexpr int kBufferFlags = 0x00020000;   // raw 32-bit buffer descriptor, word 3
 // Cache policy of the loads that stream data read once (KV pages, the race's logit rows):
 // non-temporal, i.e. the lines are first in line for replacement in the L2.  Without it the
@@ -934,9 +933,10 @@ __device__ __forceinline__ void final_role(const RejectParams &p, int b, RejectS
 // ===========================================================================
 // Attention half
 // ===========================================================================
+template <int D>
 struct PageRegs {
-    u32x4 k[4];  // k[kk]: token n, dims 32*kk + 8g .. +7
-    u32x4 v[4];  // v[pp]: dims 32*pp + n (low half) and 32*pp + 16 + n (high half), tokens 4g .. 4g+3
+    u32x4 k[D / 32];  // k[kk]: token n, dims 32*kk + 8g .. +7
+    u32x4 v[D / 32];  // v[pp]: dims 32*pp + n (low half) and 32*pp + 16 + n (high half), tokens 4g .. 4g+3
 };
 
 // The query rows and the output tile pass through LDS so that global memory sees them as
@@ -944,8 +944,8 @@ struct PageRegs {
 // matrix-operand layout, once per wavefront: with 32 to 48 query rows per KV head (grouped
 // heads) these requests were a fifth of all the block's memory requests, and the launch is
 // bound by requests as much as by bytes.  Rows are padded against bank conflicts.
-constexpr int kQStride = kD * 2 + 16;   // bytes per bf16 query row in LDS
-constexpr int kOStride = kD * 4 + 16;   // bytes per fp32 output row in LDS
+constexpr int q_stride(int D) { return D * 2 + 16; }   // bytes per bf16 query row in LDS
+constexpr int o_stride(int D) { return D * 4 + 16; }   // bytes per fp32 output row in LDS
 
 // Wave groups.  A block's four wavefronts form WG groups of PW = 4 / WG wavefronts.  Each group
 // owns NT 16-row tiles of the query rows of one (request, KV head) and walks ALL pages of the
@@ -964,13 +964,13 @@ constexpr int kOStride = kD * 4 + 16;   // bytes per fp32 output row in LDS
 constexpr int kVtRowBytes = kD * 2 + 16;
 constexpr int kVtWaveBytes = SPEC_BLOCK_SIZE * kVtRowBytes;
 
-template <int NT, int WG, bool TM = false>
+template <int NT, int WG, bool TM = false, int D = kD>
 struct AttnShared {
     static constexpr int kRowsMax = WG * NT * 16;
     union {
-        f32x4 acc[2][NT][8][kWave];               // epilogue: partial results of the wavefronts being merged
-        unsigned char q[kRowsMax * kQStride];     // prologue: the block's query rows
-        unsigned char o[WG == 1 ? NT * 16 * kOStride : 16];   // epilogue of an unsplit request (one group): the output tile
+        f32x4 acc[2][NT][D / 16][kWave];          // epilogue: partial results of the wavefronts being merged
+        unsigned char q[kRowsMax * q_stride(D)];  // prologue: the block's query rows
+        unsigned char o[WG == 1 ? NT * 16 * o_stride(D) : 16];   // epilogue of an unsplit request (one group): the output tile
     };
     float m[2][NT][kWave];
     float l[2][NT][kWave];
@@ -990,12 +990,24 @@ struct OrderTable {
 
 // VAR: 0 = pages in the matrix-operand layout, softmax weights fed as bf16 high + low parts;
 //      1 = the same with the weights as one bf16 (an experiment switch);
-//      2 = token-major pages (V transposed through LDS), weights as high + low parts.
+//      2 = token-major pages (V transposed through LDS), weights as high + low parts;
+//      3 = as 0 with a head dim of 64 (all others: 128).
+constexpr int head_dim_of(int VAR) { return VAR == 3 ? 64 : kD; }
+
 template <int NT, int WG, int VAR>
-__device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order, int item, AttnShared<NT, WG, VAR == 2> &sh)
+__device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order, int item,
+                                          AttnShared<NT, WG, VAR == 2, head_dim_of(VAR)> &sh)
 {
     constexpr bool SPLIT_P = VAR != 1;
     constexpr bool TM = VAR == 2;
+    constexpr int D = head_dim_of(VAR);
+    constexpr int KK = D / 32;                        // 32-dim steps of the score product = 1 KB loads per K or V page
+    constexpr int MT = D / 16;                        // 16-dim slices of the output
+    constexpr int kQStride = q_stride(D), kOStride = o_stride(D);
+    constexpr int kPageHeadBytes = SPEC_BLOCK_SIZE * D * 2;   // one (page, KV head) of K or of V: 4096 at D = 128
+    constexpr int QP = D / 8;                         // 16-byte pieces of a bf16 query row
+    constexpr int QI = (NT * WG * 16 * QP + kThreads - 1) / kThreads;   // ... of all the block's rows, per thread
+    static_assert(!TM || D == kD, "token-major pages: head dim 128 only");
     constexpr int PW = kWaves / WG;   // wavefronts that share the pages of a group between them
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -1063,18 +1075,18 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
 
     // Q: the block fetches its query rows once, 16 bytes per thread and consecutive threads
     // along a row (the heads of a group are adjacent in memory), and leaves them in LDS
-    u32x4 qpiece[NT * WG];
+    u32x4 qpiece[QI];
 #pragma unroll
-    for (int i = 0; i < NT * WG; ++i) {
-        const int piece = tid + i * kThreads;   // 16 pieces per row
-        const int r = piece >> 4, c = piece & 15;
+    for (int i = 0; i < QI; ++i) {
+        const int piece = tid + i * kThreads;   // QP pieces per row
+        const int r = piece / QP, c = piece % QP;
         qpiece[i] = (u32x4){0u, 0u, 0u, 0u};
         if (r < rows) {
             const size_t rh = (size_t)(row0 + r / group) * p.Hq + kvh * group + r % group;
-            qpiece[i] = *reinterpret_cast<const u32x4 *>(static_cast<const char *>(p.q) + rh * (kD * 2) + c * 16);
+            qpiece[i] = *reinterpret_cast<const u32x4 *>(static_cast<const char *>(p.q) + rh * (D * 2) + c * 16);
         }
     }
-    bf16x8 qreg[NT][4];   // filled from LDS below
+    bf16x8 qreg[NT][KK];   // filled from LDS below
     int limit[NT];     // each lane's last visible key
     int out_row[NT];   // packed (token row * Hq + head) of this lane's query row, -1 if padding
 #pragma unroll
@@ -1100,7 +1112,7 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
     const int my_pages = (npages > pw && grp_rows > 0) ? (npages - pw + PW - 1) / PW : 0;
     const int lane_off = lane * 16;
 
-    auto load_page = [&](int it, PageRegs &r) {   // it-th page of this wavefront
+    auto load_page = [&](int it, PageRegs<D> &r) {   // it-th page of this wavefront
         const int entry = __builtin_amdgcn_readlane(bt, it < my_pages ? it : 0);
         const bool valid = it < my_pages && entry >= 0;
         const int page = valid ? entry : 0;
@@ -1112,32 +1124,32 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
         if constexpr (TM) {
             // K: token n16, dims 32 i + 8 g .. + 7 sit at n16 * 256 + 64 i + 16 g
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-                r.k[i] = __builtin_amdgcn_raw_buffer_load_b128(kd, n16 * (kD * 2) + g * 16, i * 64, kStreamPolicy);
+            for (int i = 0; i < KK; ++i)
+                r.k[i] = __builtin_amdgcn_raw_buffer_load_b128(kd, n16 * (D * 2) + g * 16, i * 64, kStreamPolicy);
         } else {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) r.k[i] = __builtin_amdgcn_raw_buffer_load_b128(kd, lane_off, i * 1024, kStreamPolicy);
+            for (int i = 0; i < KK; ++i) r.k[i] = __builtin_amdgcn_raw_buffer_load_b128(kd, lane_off, i * 1024, kStreamPolicy);
         }
         // V: in operand order already, or (token-major) as whole rows: lane L holds token 4 i + L / 16, dims 8 (L % 16) .. + 7
 #pragma unroll
-        for (int i = 0; i < 4; ++i) r.v[i] = __builtin_amdgcn_raw_buffer_load_b128(vd, lane_off, i * 1024, kStreamPolicy);
+        for (int i = 0; i < KK; ++i) r.v[i] = __builtin_amdgcn_raw_buffer_load_b128(vd, lane_off, i * 1024, kStreamPolicy);
     };
 
-    f32x4 acc[NT][8];
+    f32x4 acc[NT][MT];
     float m_run[NT], l_run[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
         m_run[nt] = kEmptyMax;
         l_run[nt] = 0.0f;
 #pragma unroll
-        for (int mt = 0; mt < 8; ++mt) acc[nt][mt] = (f32x4){0.0f, 0.0f, 0.0f, 0.0f};
+        for (int mt = 0; mt < MT; ++mt) acc[nt][mt] = (f32x4){0.0f, 0.0f, 0.0f, 0.0f};
     }
 
     const int first_masked_token = L - q_len + 1;  // keys from here on are hidden from some row (or past the end)
 
     // Software pipeline: the loads of the next DEPTH pages are in flight while a page is
     // consumed.  The ring is indexed statically (the loop is unrolled by its length).
-    auto consume = [&](PageRegs &cur, int pi) {
+    auto consume = [&](PageRegs<D> &cur, int pi) {
         const int page_tok = tok0 + pi * SPEC_BLOCK_SIZE;
         const bool need_mask = page_tok + SPEC_BLOCK_SIZE > first_masked_token;
         const int tbase = page_tok + 4 * g;
@@ -1177,7 +1189,7 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
             const uint32_t lo = nvalid >= 2 ? 0xFFFFFFFFu : (nvalid == 1 ? 0x0000FFFFu : 0u);
             const uint32_t hi = nvalid >= 4 ? 0xFFFFFFFFu : (nvalid == 3 ? 0x0000FFFFu : 0u);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
+            for (int i = 0; i < KK; ++i) {
                 cur.v[i].x &= lo; cur.v[i].y &= hi;
                 cur.v[i].z &= lo; cur.v[i].w &= hi;
             }
@@ -1188,7 +1200,7 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
             if (nt > 0 && nt * 16 >= grp_rows) continue;   // a tile this request has no rows for (the same for the whole wavefront)
             f32x4 s = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk)
+            for (int kk = 0; kk < KK; ++kk)
                 s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, cur.k[kk]), qreg[nt][kk], s, 0, 0, 0);
             // (the softmax scale, folded with log2 e, is applied inside the exponent's fused
             // multiply-add below; the maximum commutes with it, the scale being positive)
@@ -1211,7 +1223,7 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
                 const float alpha = fast_exp2(m_run[nt] - m_new);
                 l_run[nt] *= alpha;
 #pragma unroll
-                for (int mt = 0; mt < 8; ++mt) acc[nt][mt] *= alpha;
+                for (int mt = 0; mt < MT; ++mt) acc[nt][mt] *= alpha;
                 m_run[nt] = m_new;
             }
             l_run[nt] += (pr[0] + pr[1]) + (pr[2] + pr[3]);
@@ -1219,7 +1231,7 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
             bf16x4 p_lo;
             if (SPLIT_P) p_lo = __builtin_convertvector(pr - __builtin_convertvector(p_hi, f32x4), bf16x4);
 #pragma unroll
-            for (int mt = 0; mt < 8; ++mt) {
+            for (int mt = 0; mt < MT; ++mt) {
                 const u32x4 vv = cur.v[mt >> 1];
                 const u32x2 half = (mt & 1) ? (u32x2){vv.z, vv.w} : (u32x2){vv.x, vv.y};
                 const bf16x4 va = __builtin_bit_cast(bf16x4, half);
@@ -1235,19 +1247,23 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
     // wait the compiler emits waits for nothing else), then issue the other batch's loads,
     // then do the arithmetic, which needs no further wait.
     constexpr int P = 1;   // pages per batch: two bring nothing once the launch keeps the memory system busy
-    PageRegs batch_a[P], batch_b[P];
-    auto load_batch = [&](int it, PageRegs(&r)[P]) {
+    PageRegs<D> batch_a[P], batch_b[P];
+    auto load_batch = [&](int it, PageRegs<D>(&r)[P]) {
 #pragma unroll
         for (int j = 0; j < P; ++j) load_page(it + j, r[j]);
     };
-    auto arrived = [&](PageRegs(&r)[P]) {
+    auto arrived = [&](PageRegs<D>(&r)[P]) {
 #pragma unroll
-        for (int j = 0; j < P; ++j)
-            asm volatile("" ::"v"(r[j].k[0]), "v"(r[j].k[1]), "v"(r[j].k[2]), "v"(r[j].k[3]), "v"(r[j].v[0]),
-                         "v"(r[j].v[1]), "v"(r[j].v[2]), "v"(r[j].v[3])
-                         : "memory");
+        for (int j = 0; j < P; ++j) {
+            if constexpr (KK == 4)
+                asm volatile("" ::"v"(r[j].k[0]), "v"(r[j].k[1]), "v"(r[j].k[2]), "v"(r[j].k[3]), "v"(r[j].v[0]),
+                             "v"(r[j].v[1]), "v"(r[j].v[2]), "v"(r[j].v[3])
+                             : "memory");
+            else
+                asm volatile("" ::"v"(r[j].k[0]), "v"(r[j].k[1]), "v"(r[j].v[0]), "v"(r[j].v[1]) : "memory");
+        }
     };
-    auto consume_batch = [&](PageRegs(&r)[P], int it) {
+    auto consume_batch = [&](PageRegs<D>(&r)[P], int it) {
 #pragma unroll
         for (int j = 0; j < P; ++j)
             if (it + j < my_pages) consume(r[j], pw + PW * (it + j));
@@ -1256,15 +1272,16 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
 
     // Q as the B operand of S^T = K Q^T, out of LDS (the first pages are on their way)
 #pragma unroll
-    for (int i = 0; i < NT * WG; ++i) {
+    for (int i = 0; i < QI; ++i) {
         const int piece = tid + i * kThreads;
-        *reinterpret_cast<u32x4 *>(sh.q + (piece >> 4) * kQStride + (piece & 15) * 16) = qpiece[i];
+        if (QI * kThreads == NT * WG * 16 * QP || piece < NT * WG * 16 * QP)
+            *reinterpret_cast<u32x4 *>(sh.q + (piece / QP) * kQStride + (piece % QP) * 16) = qpiece[i];
     }
     __syncthreads();
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk)
+        for (int kk = 0; kk < KK; ++kk)
             qreg[nt][kk] = *reinterpret_cast<const bf16x8 *>(sh.q + (row_lo + nt * 16 + n16) * kQStride + kk * 64 + g * 16);
     }
     __syncthreads();   // the epilogue reuses this memory
@@ -1289,7 +1306,7 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
 #pragma unroll
-            for (int mt = 0; mt < 8; ++mt) sh.acc[buf][nt][mt][lane] = acc[nt][mt];
+            for (int mt = 0; mt < MT; ++mt) sh.acc[buf][nt][mt][lane] = acc[nt][mt];
             sh.m[buf][nt][lane] = m_run[nt];
             sh.l[buf][nt][lane] = l_run[nt];
         }
@@ -1305,7 +1322,7 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
             l_run[nt] = l_run[nt] * wa + lo * wb;
             m_run[nt] = mn;
 #pragma unroll
-            for (int mt = 0; mt < 8; ++mt) acc[nt][mt] = acc[nt][mt] * wa + sh.acc[buf][nt][mt][lane] * wb;
+            for (int mt = 0; mt < MT; ++mt) acc[nt][mt] = acc[nt][mt] * wa + sh.acc[buf][nt][mt][lane] * wb;
         }
     };
     if constexpr (WG == 1) {          // 2,3 -> 0,1 then 1 -> 0 (the last step below, by wavefront 0)
@@ -1334,16 +1351,17 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
                 for (int nt = 0; nt < NT; ++nt) {
                     const float inv = 1.0f / l_run[nt];
 #pragma unroll
-                    for (int mt = 0; mt < 8; ++mt)
+                    for (int mt = 0; mt < MT; ++mt)
                         *reinterpret_cast<f32x4 *>(sh.o + (nt * 16 + n16) * kOStride + mt * 64 + g * 16) = acc[nt][mt] * inv;
                 }
             }
             __syncthreads();
-            for (int piece = tid; piece < rows * 32; piece += kThreads) {   // 32 pieces per row
-                const int r = piece >> 5, c = piece & 31;
+            constexpr int OP = D / 4;   // 16-byte pieces of an fp32 output row
+            for (int piece = tid; piece < rows * OP; piece += kThreads) {
+                const int r = piece / OP, c = piece % OP;
                 const size_t rh = (size_t)(row0 + r / group) * p.Hq + kvh * group + r % group;
                 __builtin_nontemporal_store(*reinterpret_cast<const f32x4 *>(sh.o + r * kOStride + c * 16),
-                                            reinterpret_cast<f32x4 *>(p.out + rh * kD + c * 4));
+                                            reinterpret_cast<f32x4 *>(p.out + rh * D + c * 4));
             }
         } else if (lead) {
             // several groups: each group's first wavefront writes its rows itself (a lane holds four
@@ -1353,9 +1371,9 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
                 if (out_row[nt] < 0) continue;
                 const float inv = 1.0f / l_run[nt];
 #pragma unroll
-                for (int mt = 0; mt < 8; ++mt)
+                for (int mt = 0; mt < MT; ++mt)
                     __builtin_nontemporal_store(acc[nt][mt] * inv,
-                                                reinterpret_cast<f32x4 *>(p.out + (size_t)out_row[nt] * kD + mt * 16 + 4 * g));
+                                                reinterpret_cast<f32x4 *>(p.out + (size_t)out_row[nt] * D + mt * 16 + 4 * g));
             }
         }
         return;
@@ -1368,9 +1386,9 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
         for (int nt = 0; nt < NT; ++nt) {
             if (out_row[nt] < 0) continue;
             const size_t slot = (size_t)out_row[nt] * p.max_chunks + chunk;
-            unsigned long long *dst = reinterpret_cast<unsigned long long *>(p.ws_acc + slot * kD + 4 * g);
+            unsigned long long *dst = reinterpret_cast<unsigned long long *>(p.ws_acc + slot * D + 4 * g);
 #pragma unroll
-            for (int mt = 0; mt < 8; ++mt) {
+            for (int mt = 0; mt < MT; ++mt) {
                 publish_u64(dst + 8 * mt + 0, pack_f32x2(acc[nt][mt][0], acc[nt][mt][1]));
                 publish_u64(dst + 8 * mt + 1, pack_f32x2(acc[nt][mt][2], acc[nt][mt][3]));
             }
@@ -1399,6 +1417,7 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
     constexpr int GROUP = 8;   // chunks merged per pass (16 per pass spill 200 to 340 bytes per lane)
     constexpr int RB = NT >= 2 ? 2 : 1;   // rows in flight per half wavefront (one row tile: at most two passes anyway, and registers are tight)
     const int half = lane >> 5, l32 = lane & 31;
+    const bool dims_on = 4 * l32 < D;   // (a head dim of 64 keeps half of the lanes busy)
     for (int r0 = 2 * wave + half; r0 < rows; r0 += 2 * kWaves * RB) {
         bool rv[RB];
         size_t rh[RB];
@@ -1413,7 +1432,7 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
             rh[j] = (size_t)(row0 + rr / group) * p.Hq + kvh * group + rr % group;
             const size_t base = rh[j] * p.max_chunks;
             ml[j] = reinterpret_cast<const unsigned long long *>(p.ws_ml) + base;
-            pa[j] = reinterpret_cast<const unsigned long long *>(p.ws_acc) + base * (kD / 2) + 2 * l32;
+            pa[j] = reinterpret_cast<const unsigned long long *>(p.ws_acc) + base * (D / 2) + 2 * l32;
             mx[j] = kEmptyMax;
             denom[j] = 0.0f;
             o[j] = (f32x4){0.0f, 0.0f, 0.0f, 0.0f};
@@ -1426,8 +1445,8 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
                 for (int c = 0; c < GROUP; ++c) {
                     const bool on = rv[j] && c0 + c < nchunks;
                     mlv[j][c] = on ? fetch_u64(ml[j] + c0 + c) : pack_f32x2(kEmptyMax, 0.0f);
-                    a0[j][c] = on ? fetch_u64(pa[j] + (size_t)(c0 + c) * (kD / 2)) : 0ull;
-                    a1[j][c] = on ? fetch_u64(pa[j] + (size_t)(c0 + c) * (kD / 2) + 1) : 0ull;
+                    a0[j][c] = on && dims_on ? fetch_u64(pa[j] + (size_t)(c0 + c) * (D / 2)) : 0ull;
+                    a1[j][c] = on && dims_on ? fetch_u64(pa[j] + (size_t)(c0 + c) * (D / 2) + 1) : 0ull;
                 }
             }
 #pragma unroll
@@ -1452,7 +1471,7 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
         }
 #pragma unroll
         for (int j = 0; j < RB; ++j)
-            if (rv[j]) *reinterpret_cast<f32x4 *>(p.out + rh[j] * kD + 4 * l32) = o[j] * (1.0f / denom[j]);
+            if (rv[j] && dims_on) *reinterpret_cast<f32x4 *>(p.out + rh[j] * D + 4 * l32) = o[j] * (1.0f / denom[j]);
     }
 }
 
@@ -1560,7 +1579,7 @@ __global__ __launch_bounds__(kThreads, 2) void spec_step_kernel(StepArgs args)
         }
     }
     if constexpr (HAS_ATTN) {
-        __shared__ AttnShared<NT, WG, VAR == 2> ash;
+        __shared__ AttnShared<NT, WG, VAR == 2, head_dim_of(VAR)> ash;
         OrderTable order;
         order.n = args.order.n;
         order.pairs = (uniform_u32_ptr)((const char __attribute__((address_space(4))) *)__builtin_amdgcn_kernarg_segment_ptr() +
@@ -1624,9 +1643,11 @@ hipError_t launch(const AttnParams &ap, const RejectParams &rp, int n_stat, int 
     };
     if constexpr (HAS_ATTN) {
         if (ap.kv_layout == SPEC_KV_TOKEN_MAJOR) return go(std::integral_constant<int, 2>());
-        // (the single-bf16 experiment exists for one wave group only)
-        if constexpr (WG == 1)
+        // (a head dim of 64 and the single-bf16 experiment exist for one wave group only)
+        if constexpr (WG == 1) {
+            if (ap.d == 64) return go(std::integral_constant<int, 3>());
             if (!ap.split_p) return go(std::integral_constant<int, 1>());
+        }
     }
     return go(std::integral_constant<int, 0>());
 }
@@ -1658,7 +1679,8 @@ hipError_t launch_step_fused(const AttnParams *attn, int row_tiles, const Reject
         const bool shape_ok = (ap.row_groups == 1 && row_tiles >= 1 && row_tiles <= 3) ||
                               ((ap.row_groups == 2 || ap.row_groups == 4) && (row_tiles == 2 || row_tiles == 3));
         // (a wavefront keeps the block-table entries of its pages one per lane)
-        if (ap.d != kD || !shape_ok || ap.chunk_tokens > 4096 / ap.row_groups || ap.chunk_tokens % SPEC_BLOCK_SIZE != 0 ||
+        const bool dim_ok = ap.d == kD || (ap.d == 64 && ap.row_groups == 1 && ap.kv_layout == SPEC_KV_MFMA);
+        if (!dim_ok || !shape_ok || ap.chunk_tokens > 4096 / ap.row_groups || ap.chunk_tokens % SPEC_BLOCK_SIZE != 0 ||
             ap.capacity_tokens > ap.chunk_tokens * ap.max_chunks ||
             (ap.fused_combine && ap.max_chunks > kMaxFusedChunks) || (order != nullptr && order->n != 0 && order->n != ap.B))
             return hipErrorInvalidValue;

@@ -191,6 +191,38 @@ def test_token_major_pages_on_the_matrix_path(harness, name, kw, tiles):
     print("%s token-major: attn err %.2e" % (name, err))
 
 
+D64_CASES = [
+    # name, kwargs, row tiles, tuning switch
+    ("d64_mha", dict(B=3, Hq=4, Hkv=4, d=64, kv_len=[37, 16, 300], k=[3, 0, 8]), 1, None),
+    ("d64_gqa4_split", dict(B=3, Hq=8, Hkv=2, d=64, kv_len=[3000, 517, 1999], k=[7, 2, 5]), 2, None),
+    ("d64_gqa8", dict(B=2, Hq=16, Hkv=2, d=64, kv_len=[700, 90], k=[5, 4]), 3, None),
+    ("d64_many_chunks", dict(B=2, Hq=8, Hkv=2, d=64, kv_len=[1500, 260], k=[8, 1]), 3, ("SPEC_VERIFY_CHUNK", 64)),    # 24 chunks: three merge passes
+    ("d64_merge_launch", dict(B=2, Hq=4, Hkv=2, d=64, kv_len=[4500, 300], k=[2, 5]), 1, ("SPEC_VERIFY_CHUNK", 64)),    # 71 chunks: merged by a launch of its own
+]
+
+
+@pytest.mark.parametrize("name,kw,tiles,switch", D64_CASES, ids=[c[0] for c in D64_CASES])
+def test_head_dim_64_on_the_matrix_path(harness, tuning, name, kw, tiles, switch):
+    """bf16 with a head dim of 64 in the matrix-operand page layout: half the matrix instructions per page,
+    2 KB per (page, KV head); unsplit, split with the in-kernel merge, and split with the merge launch."""
+    print("case head dim 64", name, flush=True)
+    if switch:
+        tuning(*switch)
+    w = W.make_workload(name, V=64, dtype="bf16", draft_std=2.0, sigma=1.0, data_seed=zlib.crc32(name.encode()) % 1000,
+                        philox_seed=3, **kw)
+    ds = harness.DeviceStep(w, kv_layout=sv.KV_MFMA)
+    plan = ds.plan()
+    assert plan["attn_path"] == sv.PATH_MFMA and plan["row_tiles"] == tiles and plan["row_groups"] == 1, plan
+    ds.run_attn()
+    err = check_attn(w, ds.results()["out"])
+    ds.out.fill_(float("nan"))
+    ds.run_step()
+    res = ds.results()
+    check_attn(w, res["out"])
+    check_reject(w, res)
+    print("%s: attn err %.2e, plan %s" % (name, err, plan))
+
+
 def test_counters_accumulate_and_runs_are_deterministic(harness):
     print("case determinism", flush=True)
     w = W.config("c2", B=2, L_scale=0.25)
