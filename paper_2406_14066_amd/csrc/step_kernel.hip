@@ -1246,7 +1246,9 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
     // about to be consumed (at that point it is the only one outstanding, so the full
     // wait the compiler emits waits for nothing else), then issue the other batch's loads,
     // then do the arithmetic, which needs no further wait.
-    constexpr int P = 1;   // pages per batch: two bring nothing once the launch keeps the memory system busy
+    // pages per batch: two bring nothing once the launch keeps the memory system busy, except with the
+    // half-size pages of a head dim of 64 (the same bytes in flight per wavefront as at 128)
+    constexpr int P = D == 64 ? 2 : 1;
     PageRegs<D> batch_a[P], batch_b[P];
     auto load_batch = [&](int it, PageRegs<D>(&r)[P]) {
 #pragma unroll
