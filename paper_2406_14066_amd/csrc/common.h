@@ -108,6 +108,8 @@ struct RejectParams {
     uint32_t generation;
     int32_t early_stop;                  // statistics in position order, rows after a request's first rejection are not read (see stats_role)
     int32_t uniform_k;                   // with early_stop: every request's draft length
+    int32_t short_naps;                  // a small launch: the bounded waits poll at short intervals at first
+    int32_t reserved;
     const float *target_logits, *draft_logits;
     const int32_t *draft_tokens, *cu_q_len;
     int32_t *accepted_len, *next_token, *out_tokens;
@@ -120,7 +122,7 @@ struct RejectParams {
     unsigned long long *race_info;       // [B]
     const unsigned long long *step_device;   // if not null: the Philox step counter, read when the kernel runs
 };
-static_assert(sizeof(RejectParams) == 16 * 4 + 16 * 8, "RejectParams has padding");
+static_assert(sizeof(RejectParams) == 18 * 4 + 16 * 8, "RejectParams has padding");
 
 // Order in which the attention items take the requests (longest first), passed as a
 // kernel argument.  n == 0: the given order.

@@ -651,6 +651,11 @@ RejectParams reject_params(const spec_reject_args *r, const RejectPlan &pl, char
     p.race_segments = pl.race_segments; p.race_seg_len = pl.race_seg_len;
     p.early_stop = pl.early_stop; p.uniform_k = pl.uniform_k;
     p.spin_limit = tuning().spin_limit;
+    {
+        // (a launch of at most one rejection block per compute unit counts as small)
+        const int64_t rows = r->accept_mode == SPEC_ACCEPT_SAMPLE ? 2 * (int64_t)r->T - r->B : r->T;
+        p.short_naps = rows * pl.stat_segments + (int64_t)r->B * (pl.race_segments + 1) <= compute_units() ? 1 : 0;
+    }
     p.stats = reinterpret_cast<unsigned long long *>(ws + pl.stats_off);
     p.race_partial = reinterpret_cast<unsigned long long *>(ws + pl.partial_off);
     p.race_info = p.race_partial + (size_t)r->B * pl.race_segments * 2;

@@ -469,14 +469,15 @@ __device__ __forceinline__ void race_segment(const RejectParams &p, const float 
 // Bounded wait until `ready` holds for every thread of the block (block-wide AND).
 // `probe` re-evaluates the condition; returns false if the limit ran out.
 template <typename F>
-__device__ __forceinline__ bool wait_all(int spin_limit, F probe)
+__device__ __forceinline__ bool wait_all(const RejectParams &p, F probe)
 {
-    for (int spin = 0; spin < spin_limit; ++spin) {
+    for (int spin = 0; spin < p.spin_limit; ++spin) {
         if (__syncthreads_and(probe() ? 1 : 0)) return true;
-        // (short naps first: in a small launch the data is a poll or two away and a long nap would be
-        // most of the wait; in a large one the waiting blocks must not crowd the memory system)
-        if (spin < 4) __builtin_amdgcn_s_sleep(2);
-        else if (spin < 8) __builtin_amdgcn_s_sleep(8);
+        // In a small launch the data is a poll or two away and a long nap would be most of the wait:
+        // short naps first.  In a large one many blocks wait at once and their polls compete with the
+        // streams (short naps there: the 7B- and 70B-shaped steps 0.5 to 0.8% slower).
+        if (p.short_naps && spin < 4) __builtin_amdgcn_s_sleep(2);
+        else if (p.short_naps && spin < 8) __builtin_amdgcn_s_sleep(8);
         else __builtin_amdgcn_s_sleep(32);
     }
     return false;
@@ -513,7 +514,7 @@ __device__ __forceinline__ bool accept_phase(const RejectParams &p, int b, Rejec
     }
 
     // poll and fetch in one: every word carries its own tag
-    const bool ok = wait_all(p.spin_limit, [&] {
+    const bool ok = wait_all(p, [&] {
         bool mine = true;
         for (int i = tid; i < nstat; i += kThreads) {
             const int ri = i / p.stat_segments;
@@ -581,7 +582,7 @@ __device__ __forceinline__ bool greedy_prefix(const RejectParams &p, int b, int 
     const int row_t0 = uniform_load(p.cu_q_len, b);
     const int row_d0 = row_t0 - b;
     const int nstat = npos * p.stat_segments;
-    const bool ok = wait_all(p.spin_limit, [&] {
+    const bool ok = wait_all(p, [&] {
         bool mine = true;
         for (int i = tid; i < nstat; i += kThreads) {
             const int ri = i / p.stat_segments;
@@ -783,7 +784,7 @@ __device__ __forceinline__ void greedy_final(const RejectParams &p, int b, Rejec
     const int k = uniform_load(p.cu_q_len, b + 1) - row_t0 - 1;
     const int row_d0 = row_t0 - b;
     const int nstat = (k + 1) * p.stat_segments;
-    const bool ok = wait_all(p.spin_limit, [&] {
+    const bool ok = wait_all(p, [&] {
         bool mine = true;
         for (int i = tid; i < nstat; i += kThreads) {
             const int ri = i / p.stat_segments;
@@ -855,7 +856,7 @@ __device__ __forceinline__ void final_role(const RejectParams &p, int b, RejectS
     float best_score = -1.0f;
     int best_id = 0x7FFFFFFF;
     uint32_t info = 0;
-    const bool ok = wait_all(p.spin_limit, [&] {
+    const bool ok = wait_all(p, [&] {
         bool mine = true;
         if (tid < p.race_segments) {
             const unsigned long long w0 = fetch_u64(part + 2 * tid), w1 = fetch_u64(part + 2 * tid + 1);
@@ -1499,7 +1500,7 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
 //    attention row iff floor((r+1) * rows_attn / rows) > floor(r * rows_attn / rows).
 struct GridSplit {
     int n_stat, n_reject, n_attn;
-    int attn_first;        // 1: attention items first, 0: mixed, 2: rejection items first
+    int attn_first;        // 1: attention items first, 0: mixed (with no attention rows in the mixed part: rejection items first)
     int rows_attn_mixed;   // attention rows among which the rejection rows are spread; the other attention rows follow
     int reject_cols;       // positions of a row of 8 blocks that carry rejection items: all 8, or the 4 even ones
 };
@@ -1522,12 +1523,7 @@ __global__ __launch_bounds__(kThreads, 2) void spec_step_kernel(StepArgs args)
     int item = blockIdx.x;
     bool is_attn = HAS_ATTN;
     if constexpr (HAS_ATTN && HAS_REJECT) {
-        if (gs.attn_first == 2) {   // the few rejection items, then the attention items
-            const int n_reject_rows8 = (gs.n_reject + kXcds - 1) / kXcds * kXcds;
-            is_attn = item >= n_reject_rows8;
-            if (is_attn) item -= n_reject_rows8;
-            if (item >= (is_attn ? gs.n_attn : gs.n_reject)) return;
-        } else if (gs.attn_first) {
+        if (gs.attn_first) {
             const int n_attn_rows8 = (gs.n_attn + kXcds - 1) / kXcds * kXcds;   // whole rows: positions keep their XCD
             is_attn = item < n_attn_rows8;
             if (is_attn) {
@@ -1613,7 +1609,9 @@ hipError_t launch(const AttnParams &ap, const RejectParams &rp, int n_stat, int 
     // chain is what the launch waits for: its items go first, ahead of the attention blocks, which
     // lose a few microseconds of dispatch to them.  (Four requests of 512 tokens: 21.2 -> 18.0 us;
     // sixteen with 64/8 heads: 28.3 -> 24.6 us; two of 2048 tokens: 22.4 -> 19.2 us.)
-    if (HAS_ATTN && HAS_REJECT && n_reject <= ap.reject_first_limit) gs.attn_first = 2;
+    // (In terms of the mixed order: no attention rows among the rejection rows.)
+    const bool reject_first = HAS_ATTN && HAS_REJECT && n_reject <= ap.reject_first_limit;
+    if (reject_first) gs.attn_first = 0;
     const bool mixed = HAS_ATTN && HAS_REJECT && !gs.attn_first;
     // The rejection stages of a request wait for each other, so the last rejection item sits
     // well before the end of the grid: the tail of the launch is attention only.
@@ -1621,6 +1619,7 @@ hipError_t launch(const AttnParams &ap, const RejectParams &rp, int n_stat, int 
     gs.rows_attn_mixed = (int)(rows_attn_all * (double)ap.reject_span);
     if (gs.rows_attn_mixed < 1) gs.rows_attn_mixed = 1;
     if (gs.rows_attn_mixed > rows_attn_all) gs.rows_attn_mixed = rows_attn_all;
+    if (reject_first) gs.rows_attn_mixed = 0;
     // XCDs 1, 3, 5, 7 of this device stream from memory some 6% slower than XCDs 0, 2, 4, 6 (block
     // traces of equal attention blocks), and a launch ends with its slowest XCD.  When there is at
     // most one attention block per compute unit (all resident from the start, the rejection blocks
@@ -1628,11 +1627,10 @@ hipError_t launch(const AttnParams &ap, const RejectParams &rp, int n_stat, int 
     // unit with, go to the even XCDs only: even positions of a row of 8 blocks; the odd positions
     // of such rows exit at once.  (With more attention blocks it does not pay: measured 1% slower
     // with two per compute unit, 15% slower where the rejection half is a fifth of the step.)
-    gs.reject_cols = (HAS_ATTN && HAS_REJECT && ap.reject_even_xcds && n_attn <= ap.reject_even_limit && gs.attn_first != 2) ? kXcds / 2 : kXcds;
+    gs.reject_cols = (HAS_ATTN && HAS_REJECT && ap.reject_even_xcds && n_attn <= ap.reject_even_limit && !reject_first) ? kXcds / 2 : kXcds;
     const int rows_reject = (n_reject + gs.reject_cols - 1) / gs.reject_cols;
-    const dim3 grid(gs.attn_first == 2 ? (n_reject + kXcds - 1) / kXcds * kXcds + n_attn
-                    : mixed            ? (rows_attn_all + rows_reject) * kXcds
-                                       : (HAS_ATTN && HAS_REJECT ? (rows_attn_all + rows_reject) * kXcds : n_reject + n_attn));
+    const dim3 grid(mixed ? (rows_attn_all + rows_reject) * kXcds
+                          : (HAS_ATTN && HAS_REJECT ? (rows_attn_all + rows_reject) * kXcds : n_reject + n_attn));
     // (with events the extended launch attaches them to the kernel's own begin and end)
     auto go = [&](auto var) {
         constexpr int VAR = decltype(var)::value;
