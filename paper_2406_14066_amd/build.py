@@ -23,14 +23,56 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
-def build_library(verbose: bool = False) -> str:
+# step_kernel.hip holds dozens of kernel variants; it is compiled once per part (see SPEC_STEP_PART
+# in that file), in parallel with the other sources, and the objects are linked.
+STEP_KERNEL = "step_kernel.hip"
+STEP_PARTS = 5
+
+
+def compile_jobs(objdir: str):
+    """(command, object file) for every translation unit of the library."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    tmp = LIB + ".tmp.%d" % os.getpid()
-    cmd = [hipcc] + HIPCC_FLAGS + ["-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", tmp] + sources()
-    if verbose:
-        print(" ".join(cmd))
-    subprocess.run(cmd, check=True)
-    os.replace(tmp, LIB)
+    flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+    base = [hipcc] + flags + ["-I", os.path.join(ROOT, "include"), "-I", CSRC, "-c"]
+    jobs = []
+    for src in sources():
+        stem = os.path.splitext(os.path.basename(src))[0]
+        if os.path.basename(src) == STEP_KERNEL:
+            for part in range(STEP_PARTS):
+                obj = os.path.join(objdir, "%s_part%d.o" % (stem, part))
+                jobs.append((base + ["-DSPEC_STEP_PART=%d" % part, "-o", obj, src], obj))
+        else:
+            obj = os.path.join(objdir, stem + ".o")
+            jobs.append((base + ["-o", obj, src], obj))
+    return jobs
+
+
+def build_library(verbose: bool = False) -> str:
+    import shutil
+    import tempfile
+    from concurrent.futures import ThreadPoolExecutor
+
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    objdir = tempfile.mkdtemp(prefix="spec_verify_build_")
+    try:
+        jobs = compile_jobs(objdir)
+
+        def run(job):
+            if verbose:
+                print(" ".join(job[0]))
+            subprocess.run(job[0], check=True)
+            return job[1]
+
+        with ThreadPoolExecutor(max_workers=min(len(jobs), os.cpu_count() or 4, 16)) as pool:
+            objects = list(pool.map(run, jobs))
+        tmp = LIB + ".tmp.%d" % os.getpid()
+        link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objects
+        if verbose:
+            print(" ".join(link))
+        subprocess.run(link, check=True)
+        os.replace(tmp, LIB)
+    finally:
+        shutil.rmtree(objdir, ignore_errors=True)
     return LIB
 
 

@@ -1654,6 +1654,54 @@ hipError_t launch(const AttnParams &ap, const RejectParams &rp, int n_stat, int 
 
 }  // namespace
 
+// The kernel variants of this file take over a minute to compile in one piece, so the build
+// compiles the file several times, each time with SPEC_STEP_PART set to the part whose
+// launchers it should hold (everything else of the file is shared, file-local code):
+//   0: the dispatcher below, the rejection-only kernel, one row tile    1: two row tiles
+//   2: three row tiles    3: two wave groups    4: four wave groups      (unset: all of it)
+#ifndef SPEC_STEP_PART
+#define SPEC_STEP_PART -1
+#endif
+#define SPEC_STEP_HAS_PART(k) (SPEC_STEP_PART < 0 || SPEC_STEP_PART == (k))
+
+// launchers of the (row tiles, wave groups) variants, one function each
+#define SPEC_STEP_LAUNCHER(NAME) \
+    hipError_t NAME(const AttnParams &ap, const RejectParams &rp, bool with_reject, int n_stat, int n_attn, int n_race, \
+                    const UnitOrder *order, LaunchEvents ev, hipStream_t stream)
+SPEC_STEP_LAUNCHER(launch_step_tiles1);
+SPEC_STEP_LAUNCHER(launch_step_tiles2);
+SPEC_STEP_LAUNCHER(launch_step_tiles3);
+SPEC_STEP_LAUNCHER(launch_step_tiles2_groups2);
+SPEC_STEP_LAUNCHER(launch_step_tiles3_groups2);
+SPEC_STEP_LAUNCHER(launch_step_tiles2_groups4);
+SPEC_STEP_LAUNCHER(launch_step_tiles3_groups4);
+#define SPEC_STEP_DEFINE(NAME, NT_, WG_)                                                                     \
+    SPEC_STEP_LAUNCHER(NAME)                                                                                 \
+    {                                                                                                        \
+        return with_reject ? launch<NT_, WG_, true, true>(ap, rp, n_stat, n_attn, n_race, order, ev, stream) \
+                           : launch<NT_, WG_, true, false>(ap, rp, 0, n_attn, 0, order, ev, stream);         \
+    }
+#if SPEC_STEP_HAS_PART(0)
+SPEC_STEP_DEFINE(launch_step_tiles1, 1, 1)
+#endif
+#if SPEC_STEP_HAS_PART(1)
+SPEC_STEP_DEFINE(launch_step_tiles2, 2, 1)
+#endif
+#if SPEC_STEP_HAS_PART(2)
+SPEC_STEP_DEFINE(launch_step_tiles3, 3, 1)
+#endif
+#if SPEC_STEP_HAS_PART(3)
+SPEC_STEP_DEFINE(launch_step_tiles2_groups2, 2, 2)
+SPEC_STEP_DEFINE(launch_step_tiles3_groups2, 3, 2)
+#endif
+#if SPEC_STEP_HAS_PART(4)
+SPEC_STEP_DEFINE(launch_step_tiles2_groups4, 2, 4)
+SPEC_STEP_DEFINE(launch_step_tiles3_groups4, 3, 4)
+#endif
+#undef SPEC_STEP_DEFINE
+#undef SPEC_STEP_LAUNCHER
+
+#if SPEC_STEP_HAS_PART(0)
 int step_attn_items(const AttnParams &ap)
 {
     return ap.B * ap.Hkv * ap.max_chunks;
@@ -1687,19 +1735,17 @@ hipError_t launch_step_fused(const AttnParams *attn, int row_tiles, const Reject
         n_attn = step_attn_items(ap);
     }
     if (attn == nullptr) return launch<1, 1, false, true>(ap, rp, n_stat, 0, n_race, nullptr, ev, stream);
-#define SPEC_LAUNCH_ATTN(NT_, WG_)                                                                              \
-    (reject == nullptr ? launch<NT_, WG_, true, false>(ap, rp, 0, n_attn, 0, order, ev, stream)                 \
-                       : launch<NT_, WG_, true, true>(ap, rp, n_stat, n_attn, n_race, order, ev, stream))
+    const bool with_reject = reject != nullptr;
     switch (ap.row_groups * 10 + row_tiles) {
-        case 11: return SPEC_LAUNCH_ATTN(1, 1);
-        case 12: return SPEC_LAUNCH_ATTN(2, 1);
-        case 13: return SPEC_LAUNCH_ATTN(3, 1);
-        case 22: return SPEC_LAUNCH_ATTN(2, 2);
-        case 23: return SPEC_LAUNCH_ATTN(3, 2);
-        case 42: return SPEC_LAUNCH_ATTN(2, 4);
-        default: return SPEC_LAUNCH_ATTN(3, 4);
+        case 11: return launch_step_tiles1(ap, rp, with_reject, n_stat, n_attn, n_race, order, ev, stream);
+        case 12: return launch_step_tiles2(ap, rp, with_reject, n_stat, n_attn, n_race, order, ev, stream);
+        case 13: return launch_step_tiles3(ap, rp, with_reject, n_stat, n_attn, n_race, order, ev, stream);
+        case 22: return launch_step_tiles2_groups2(ap, rp, with_reject, n_stat, n_attn, n_race, order, ev, stream);
+        case 23: return launch_step_tiles3_groups2(ap, rp, with_reject, n_stat, n_attn, n_race, order, ev, stream);
+        case 42: return launch_step_tiles2_groups4(ap, rp, with_reject, n_stat, n_attn, n_race, order, ev, stream);
+        default: return launch_step_tiles3_groups4(ap, rp, with_reject, n_stat, n_attn, n_race, order, ev, stream);
     }
-#undef SPEC_LAUNCH_ATTN
 }
+#endif   // part 0
 
 }  // namespace specv

@@ -6,6 +6,7 @@ import os
 import re
 import shutil
 import subprocess
+from concurrent.futures import ThreadPoolExecutor
 
 import pytest
 
@@ -17,34 +18,44 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 @pytest.mark.skipif(shutil.which(HIPCC) is None and not os.path.exists(HIPCC), reason="hipcc not installed")
 def test_step_kernel_uses_no_private_memory_and_keeps_its_occupancy(tmp_path):
     flags = [f for f in B.HIPCC_FLAGS if f not in ("-shared", "-fPIC")]
-    asm = tmp_path / "step.s"
-    cmd = [HIPCC] + flags + ["-I", os.path.join(B.ROOT, "include"), "-I", B.CSRC, "-Rpass-analysis=kernel-resource-usage",
-                             "-S", "--cuda-device-only", "-o", str(asm), os.path.join(B.CSRC, "step_kernel.hip")]
-    out = subprocess.run(cmd, check=True, capture_output=True, text=True).stderr
+
+    def compile_part(part):
+        # (the file is built in parts, see SPEC_STEP_PART in step_kernel.hip; so is it here)
+        asm = tmp_path / ("step_part%d.s" % part)
+        cmd = [HIPCC] + flags + ["-I", os.path.join(B.ROOT, "include"), "-I", B.CSRC, "-DSPEC_STEP_PART=%d" % part,
+                                 "-Rpass-analysis=kernel-resource-usage", "-S", "--cuda-device-only", "-o", str(asm),
+                                 os.path.join(B.CSRC, B.STEP_KERNEL)]
+        return asm, subprocess.run(cmd, check=True, capture_output=True, text=True).stderr
+
+    with ThreadPoolExecutor(max_workers=min(B.STEP_PARTS, os.cpu_count() or 4)) as pool:
+        parts = list(pool.map(compile_part, range(B.STEP_PARTS)))
     kernels = {}
     name = None
-    for line in out.splitlines():
-        m = re.search(r"Function Name: \S*spec_step_kernelILi(\d)ELi(\d)ELb(\d)ELb(\d)ELi(\d)E", line)
-        if m:
-            name = tuple(int(x) for x in m.groups())
-            kernels[name] = {}
-            continue
-        m = re.search(r"remark:\s+(VGPRs|ScratchSize \[bytes/lane\]|Occupancy \[waves/SIMD\]): (\d+)", line)
-        if m and name is not None:
-            kernels[name][m.group(1).split(" ")[0]] = int(m.group(2))
+    for _asm, out in parts:
+        for line in out.splitlines():
+            m = re.search(r"Function Name: \S*spec_step_kernelILi(\d)ELi(\d)ELb(\d)ELb(\d)ELi(\d)E", line)
+            if m:
+                name = tuple(int(x) for x in m.groups())
+                assert name not in kernels, name      # every variant lives in exactly one part
+                kernels[name] = {}
+                continue
+            m = re.search(r"remark:\s+(VGPRs|ScratchSize \[bytes/lane\]|Occupancy \[waves/SIMD\]): (\d+)", line)
+            if m and name is not None:
+                kernels[name][m.group(1).split(" ")[0]] = int(m.group(2))
     assert len(kernels) == 41, sorted(kernels)   # (row tiles, wave groups, attention, rejection, variant)
     # instructions that touch private memory, per kernel, from the assembly
     touches = {}
-    name = None
-    for line in open(asm):
-        m = re.match(r"^(\S*spec_step_kernelILi(\d)ELi(\d)ELb(\d)ELb(\d)ELi(\d)E\S*):\s", line)
-        if m:
-            name = tuple(int(x) for x in m.groups()[1:])
-            touches[name] = 0
-        elif name is not None and re.search(r"^\s+scratch_(load|store)", line):
-            touches[name] += 1
-        elif "-- End function" in line:
-            name = None
+    for asm, _out in parts:
+        name = None
+        for line in open(asm):
+            m = re.match(r"^(\S*spec_step_kernelILi(\d)ELi(\d)ELb(\d)ELb(\d)ELi(\d)E\S*):\s", line)
+            if m:
+                name = tuple(int(x) for x in m.groups()[1:])
+                touches[name] = 0
+            elif name is not None and re.search(r"^\s+scratch_(load|store)", line):
+                touches[name] += 1
+            elif "-- End function" in line:
+                name = None
     assert set(touches) == set(kernels)
     for key, r in kernels.items():
         nt, wg, has_attn, has_reject, variant = key
