@@ -364,6 +364,23 @@ def test_tuning_switches_are_read_once_and_on_reload(monkeypatch):
     assert sv.spec_verify_plan(a, None)["attn_path"] == sv.PATH_MFMA
 
 
+@pytest.mark.parametrize("B,Hq,Hkv,length,most_chunks", [
+    (1, 64, 8, 2749, 8),      # a launch bound by latencies: few chunks, however many compute units are idle
+    (1, 64, 8, 172, 1),       # ... and none below 256 tokens
+    (4, 64, 8, 204, 1),
+    (1, 32, 32, 2048, 8),
+    (1, 32, 8, 32768, 32),    # long enough for chunks of 1024 tokens: split as far as the compute units ask
+])
+def test_small_launches_are_split_sparingly(B, Hq, Hkv, length, most_chunks):
+    a = _attn(B=B, Hq=Hq, Hkv=Hkv, kv_len=(length,) * B, q_len=(3,) * B, max_blocks=(length + 15) // 16)
+    plan = sv.spec_verify_plan(a, None)
+    assert plan["attn_path"] == sv.PATH_MFMA
+    assert plan["max_chunks"] <= most_chunks, plan
+    assert plan["chunk_tokens"] >= 256 and plan["chunk_tokens"] * plan["max_chunks"] >= length, plan
+    if most_chunks > 8:
+        assert plan["max_chunks"] > 8 and plan["chunk_tokens"] >= 1024, plan
+
+
 def test_plan_is_reused_for_an_unchanged_shape_and_follows_a_changed_one():
     q_len = (3,) * 6
     a = _attn(B=6, Hq=8, Hkv=2, kv_len=(100, 200, 300, 400, 500, 600), q_len=q_len, max_blocks=64)
