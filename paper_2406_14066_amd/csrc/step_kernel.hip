@@ -119,17 +119,21 @@ __device__ __forceinline__ float4 load_streaming(const float *p)
 
 // ---------------------------------------------------------------------------
 // Tickets.  Word = generation << 32 | arrivals.  Returns how many blocks arrived
-// before this one.  The first arrival of a generation replaces whatever the word
-// held (garbage, or the leftovers of an older call).
+// before this one.  The common case is one atomic add: the word carries this call's
+// generation already.  The first arrivals of a call find something else (garbage, the
+// zero its last user left, or either plus what other early arrivals added) and replace
+// it; the last arrival, which is the one the merge waits for, is never among them.
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ uint32_t ticket_arrive(unsigned long long *ticket, uint32_t generation)
 {
-    unsigned long long cur = __hip_atomic_load(ticket, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned long long got = atomicAdd(ticket, 1ull);
+    if ((uint32_t)(got >> 32) == generation) return (uint32_t)got;
+    unsigned long long cur = got + 1ull;
     for (;;) {
-        if ((uint32_t)(cur >> 32) == generation) return (uint32_t)atomicAdd(ticket, 1ull);
         const unsigned long long first = ((unsigned long long)generation << 32) | 1ull;
         const unsigned long long seen = atomicCAS(ticket, cur, first);
         if (seen == cur) return 0u;
+        if ((uint32_t)(seen >> 32) == generation) return (uint32_t)atomicAdd(ticket, 1ull);
         cur = seen;
     }
 }
