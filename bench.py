@@ -6,8 +6,9 @@ cache, then rejection sampling with bonus token -- over one batch of seeded synt
 input that is already resident in HBM.  The headline workload is the largest of the
 named configurations that fits one GPU: c4, the 70B-shaped GQA batch (B=256, L uniform
 in [256,1024], k=2, 64/8 heads, d=128, bf16 paged KV, V=32000).  The other named
-workloads (c2, a c3 sweep point, c5) and a c4-shaped batch at k=7 (more than 48 fused
-query rows per KV head) are timed in the same run and reported under "workloads".
+workloads (c1, c2, a c3 sweep point, c5), a c4-shaped batch at k=7 (more than 48 fused
+query rows per KV head), the same steps on token-major pages and the 7B-shaped step with a
+single request (bound by latencies) are timed in the same run and reported under "workloads".
 
 KV pools and logits are rotated over several device copies so that consecutive steps
 do not find their inputs in the 256 MB last-level cache.
@@ -39,7 +40,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4", "c5", "c4_k7"],
+    ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4", "c5", "c4_k7", "c2_one_request"],
                     help="the workload of the headline figures")
     ap.add_argument("--k", type=int, default=None, help="speculation length of the c3 sweep point")
     ap.add_argument("--alpha", type=float, default=None, help="acceptance level of the c3 sweep point")
@@ -77,6 +78,10 @@ def make_workload(name, k=None, alpha=None):
     if name == "c4_k7":
         w = W.config("c4", k=7)
         w.name = "c4_k7"
+        return w
+    if name == "c2_one_request":   # the 7B-shaped step with a single request: bound by latencies, not by bytes
+        w = W.config("c2", B=1)
+        w.name = "c2_one_request"
         return w
     return W.config(name)
 
@@ -272,7 +277,7 @@ def main():
             others[w.name + "_token_major_pages"] = brief(mo, None)
             del mo
             torch.cuda.empty_cache()
-        for name, kw in [("c1", {}), ("c2", {}), ("c3", dict(k=4, alpha=0.7)), ("c5", {}), ("c4_k7", {})]:
+        for name, kw in [("c1", {}), ("c2", {}), ("c3", dict(k=4, alpha=0.7)), ("c5", {}), ("c4_k7", {}), ("c2_one_request", {})]:
             if name == args.workload:
                 continue
             wo = make_workload(name, **kw)
