@@ -235,6 +235,31 @@ def test_counters_accumulate_and_runs_are_deterministic(harness):
     np.testing.assert_array_equal(res2["counters"], 2 * res1["counters"])
 
 
+@pytest.mark.parametrize("switches", [
+    {"SPEC_VERIFY_REJECT_FIRST_LIMIT": 0},                                      # attention blocks first (or mixed) instead of rejection first
+    {"SPEC_VERIFY_ATTN_FIRST_LIMIT": 0, "SPEC_VERIFY_REJECT_FIRST_LIMIT": 0},   # rejection rows mixed among the attention rows
+    {"SPEC_VERIFY_REJECT_EVEN": 0, "SPEC_VERIFY_REJECT_FIRST_LIMIT": 0},        # rejection blocks on all XCDs
+    {"SPEC_VERIFY_TARGET_BLOCKS": 512},                                         # more, shorter chunks
+], ids=["attention_first", "mixed", "all_xcds", "more_chunks"])
+def test_the_grid_order_and_the_split_change_no_decision(harness, tuning, switches):
+    """Where a block sits in the grid is a matter of speed only: with every order the planner can
+    choose the step gives the same decisions, and the same output bits unless the split changes."""
+    print("case grid order", switches, flush=True)
+    w = W.config("c4", B=12, L_scale=0.5, V=4096)
+    ds, base = _run(harness, w, sv.KV_MFMA)
+    check_attn(w, base["out"])
+    check_reject(w, base)
+    for name, value in switches.items():
+        tuning(name, value)
+    ds2, res = _run(harness, w, sv.KV_MFMA)
+    check_attn(w, res["out"])
+    check_reject(w, res)
+    for key in ("accepted_len", "next_token", "counters"):
+        np.testing.assert_array_equal(res[key], base[key], err_msg=key)
+    if "SPEC_VERIFY_TARGET_BLOCKS" not in switches:
+        np.testing.assert_array_equal(res["out"], base["out"])
+
+
 def test_c2_full(harness):
     w = W.config("c2")
     print("case c2 full", flush=True)
