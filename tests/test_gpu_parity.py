@@ -314,6 +314,22 @@ def test_c4_full(harness):
     print("c4: attn err %.2e near ties %d min race margin %.2e" % (err, info["near_ties"], info["min_race_margin"]))
 
 
+def test_c4_shape_at_k7_full(harness, layout=sv.KV_MFMA):
+    """The c4 batch at k = 7 as bench.py times it (64 fused rows per KV head: two wave groups; statistics
+    in position order): the whole attention output and every decision against the oracle."""
+    w = W.config("c4", k=7)
+    print("case c4 at k=7 full, layout", layout, flush=True)
+    ds = harness.DeviceStep(w, kv_layout=layout)
+    plan = ds.plan()
+    assert (plan["attn_path"], plan["row_tiles"], plan["row_groups"], plan["launches"], plan["early_stop"]) == (sv.PATH_MFMA, 2, 2, 1, 1), plan
+    ds.run_step()
+    res = ds.results()
+    err = check_attn(w, res["out"])
+    info = check_reject(w, res)
+    _assert_nothing_excluded(info)
+    print("c4 at k=7: attn err %.2e near ties %d min race margin %.2e" % (err, info["near_ties"], info["min_race_margin"]))
+
+
 def test_c5_full(harness):
     w = W.config("c5")
     print("case c5 full", w.kv_len, w.q_len, flush=True)
