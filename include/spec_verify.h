@@ -39,10 +39,9 @@
  *     length and group width within the limits (up to 9 * 16 fused rows per KV
  *     head); token-major pages take the same kernel, 3 to 8% slower up to 48
  *     fused rows and about 20% slower beyond (V is transposed through LDS inside
- *     the kernel).  bf16 with d == 64 takes it in the SPEC_KV_MFMA layout up to
- *     48 fused rows.  fp32 and the other d == 64 shapes run on plain, untuned
- *     kernels (two or three launches).  spec_verify_plan tells which path a call
- *     takes.
+ *     the kernel).  bf16 with d == 64 takes it in the SPEC_KV_MFMA layout.  fp32
+ *     and d == 64 with token-major pages run on plain, untuned kernels (two or
+ *     three launches).  spec_verify_plan tells which path a call takes.
  */
 #ifndef SPEC_VERIFY_H
 #define SPEC_VERIFY_H
@@ -256,7 +255,7 @@ spec_status spec_verify_step_static(const spec_attn_args *attn, const spec_rejec
 #define SPEC_PATH_NONE 0
 #define SPEC_PATH_MFMA 1     /* matrix-instruction attention inside the one-launch step kernel */
 #define SPEC_PATH_GENERIC 2  /* scalar attention kernel, plus a merge kernel when a request is split (fp32; d = 64
-                                with token-major pages or more than 48 fused rows) */
+                                with token-major pages) */
 typedef struct {
     int32_t attn_path;       /* SPEC_PATH_* */
     int32_t row_tiles;       /* 16-row tiles of query rows per wavefront (matrix path, 1..3) */

@@ -1647,11 +1647,10 @@ hipError_t launch(const AttnParams &ap, const RejectParams &rp, int n_stat, int 
     };
     if constexpr (HAS_ATTN) {
         if (ap.kv_layout == SPEC_KV_TOKEN_MAJOR) return go(std::integral_constant<int, 2>());
-        // (a head dim of 64 and the single-bf16 experiment exist for one wave group only)
-        if constexpr (WG == 1) {
-            if (ap.d == 64) return go(std::integral_constant<int, 3>());
+        if (ap.d == 64) return go(std::integral_constant<int, 3>());
+        // (the single-bf16 experiment exists for one wave group only)
+        if constexpr (WG == 1)
             if (!ap.split_p) return go(std::integral_constant<int, 1>());
-        }
     }
     return go(std::integral_constant<int, 0>());
 }
@@ -1731,7 +1730,7 @@ hipError_t launch_step_fused(const AttnParams *attn, int row_tiles, const Reject
         const bool shape_ok = (ap.row_groups == 1 && row_tiles >= 1 && row_tiles <= 3) ||
                               ((ap.row_groups == 2 || ap.row_groups == 4) && (row_tiles == 2 || row_tiles == 3));
         // (a wavefront keeps the block-table entries of its pages one per lane)
-        const bool dim_ok = ap.d == kD || (ap.d == 64 && ap.row_groups == 1 && ap.kv_layout == SPEC_KV_MFMA);
+        const bool dim_ok = ap.d == kD || (ap.d == 64 && ap.kv_layout == SPEC_KV_MFMA);
         if (!dim_ok || !shape_ok || ap.chunk_tokens > 4096 / ap.row_groups || ap.chunk_tokens % SPEC_BLOCK_SIZE != 0 ||
             ap.capacity_tokens > ap.chunk_tokens * ap.max_chunks ||
             (ap.fused_combine && ap.max_chunks > kMaxFusedChunks) || (order != nullptr && order->n != 0 && order->n != ap.B))

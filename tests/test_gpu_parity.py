@@ -198,6 +198,8 @@ D64_CASES = [
     ("d64_gqa8", dict(B=2, Hq=16, Hkv=2, d=64, kv_len=[700, 90], k=[5, 4]), 3, None),
     ("d64_many_chunks", dict(B=2, Hq=8, Hkv=2, d=64, kv_len=[1500, 260], k=[8, 1]), 3, ("SPEC_VERIFY_CHUNK", 64)),    # 24 chunks: three merge passes
     ("d64_merge_launch", dict(B=2, Hq=4, Hkv=2, d=64, kv_len=[4500, 300], k=[2, 5]), 1, ("SPEC_VERIFY_CHUNK", 64)),    # 71 chunks: merged by a launch of its own
+    ("d64_two_groups", dict(B=3, Hq=16, Hkv=2, d=64, kv_len=[3000, 517, 1999], k=[7, 7, 6]), 2, None),                  # 64 rows: two wave groups, split requests
+    ("d64_four_groups", dict(B=2, Hq=16, Hkv=1, d=64, kv_len=[700, 90], k=[8, 8]), 3, None),                           # 144 rows: four wave groups
 ]
 
 
@@ -212,7 +214,8 @@ def test_head_dim_64_on_the_matrix_path(harness, tuning, name, kw, tiles, switch
                         philox_seed=3, **kw)
     ds = harness.DeviceStep(w, kv_layout=sv.KV_MFMA)
     plan = ds.plan()
-    assert plan["attn_path"] == sv.PATH_MFMA and plan["row_tiles"] == tiles and plan["row_groups"] == 1, plan
+    assert plan["attn_path"] == sv.PATH_MFMA and plan["row_tiles"] == tiles, plan
+    assert plan["row_groups"] == {"d64_two_groups": 2, "d64_four_groups": 4}.get(name, 1), plan
     ds.run_attn()
     err = check_attn(w, ds.results()["out"])
     ds.out.fill_(float("nan"))
