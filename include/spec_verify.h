@@ -34,14 +34,13 @@
  *   - Same inputs and same (philox_seed, philox_step) give the same outputs.
  *   - Limits: k_b <= SPEC_K_MAX, block_size == 16, d in {64, 128},
  *     Hq % Hkv == 0, Hq/Hkv <= 16, kv_len[b] >= q_len[b] >= 1.
- *   - Speed: bf16 with d == 128 runs on the matrix-instruction kernel, the whole
- *     step in one launch: with pages in the SPEC_KV_MFMA layout for every draft
- *     length and group width within the limits (up to 9 * 16 fused rows per KV
- *     head); token-major pages take the same kernel, 3 to 8% slower up to 48
- *     fused rows and about 20% slower beyond (V is transposed through LDS inside
- *     the kernel).  bf16 with d == 64 takes it in the SPEC_KV_MFMA layout.  fp32
- *     and d == 64 with token-major pages run on plain, untuned kernels (two or
- *     three launches).  spec_verify_plan tells which path a call takes.
+ *   - Speed: bf16 runs on the matrix-instruction kernel, the whole step in one
+ *     launch, for every draft length and group width within the limits (up to
+ *     9 * 16 fused rows per KV head) and both head dims: fastest with pages in
+ *     the SPEC_KV_MFMA layout; token-major pages take the same kernel, 3 to 8%
+ *     slower up to 48 fused rows and about 20% slower beyond (V is transposed
+ *     through LDS inside the kernel).  fp32 runs on plain, untuned kernels (two
+ *     or three launches).  spec_verify_plan tells which path a call takes.
  */
 #ifndef SPEC_VERIFY_H
 #define SPEC_VERIFY_H
@@ -254,8 +253,7 @@ spec_status spec_verify_step_static(const spec_attn_args *attn, const spec_rejec
  */
 #define SPEC_PATH_NONE 0
 #define SPEC_PATH_MFMA 1     /* matrix-instruction attention inside the one-launch step kernel */
-#define SPEC_PATH_GENERIC 2  /* scalar attention kernel, plus a merge kernel when a request is split (fp32; d = 64
-                                with token-major pages) */
+#define SPEC_PATH_GENERIC 2  /* scalar attention kernel, plus a merge kernel when a request is split (fp32) */
 typedef struct {
     int32_t attn_path;       /* SPEC_PATH_* */
     int32_t row_tiles;       /* 16-row tiles of query rows per wavefront (matrix path, 1..3) */

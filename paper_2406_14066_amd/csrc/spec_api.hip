@@ -324,10 +324,9 @@ AttnPlan plan_attn(const spec_attn_args *a, const Tuning &tu)
     pl.max_q_len = max_q;
     const int group = a->Hq / a->Hkv;
     const int tiles = (max_q * group + 15) / 16;
-    // bf16 runs on the matrix-instruction kernel: with d = 128 in either page layout (token-major
-    // pages have their V transposed through LDS), with d = 64 in the matrix-operand layout
-    pl.use_mfma = (a->qkv_dtype == SPEC_BF16 && !tu.force_generic &&
-                   (a->d == 128 || (a->d == 64 && a->kv_layout == SPEC_KV_MFMA))) ? 1 : 0;
+    // bf16 runs on the matrix-instruction kernel, in either page layout (token-major pages have
+    // their V transposed through LDS)
+    pl.use_mfma = (a->qkv_dtype == SPEC_BF16 && !tu.force_generic) ? 1 : 0;
     pl.row_groups = 1;
     pl.row_tiles = tiles;
     if (pl.use_mfma) {

@@ -959,15 +959,15 @@ constexpr int o_stride(int D) { return D * 4 + 16; }   // bytes per fp32 output 
 // rows) the groups of one block read the same pages at the same time, so the pages cross the
 // memory interface once and the groups find each other's loads in the compute unit's cache or
 // in flight.
-// Token-major pages ([16 tokens][128 dims] per page and KV head).  K is loaded straight into the
+// Token-major pages ([16 tokens][D dims] per page and KV head).  K is loaded straight into the
 // matrix operand order from that layout too (a lane's 16 bytes are 8 consecutive dims of one
 // token); V has to be transposed (the PV product wants, per lane, four consecutive tokens of one
 // dim): each wavefront loads its V page as whole rows (coalesced 16-byte loads), stages it in a
 // region of its own in LDS and reads it back two bytes at a time in operand order.  Token rows
-// are padded to 272 bytes: the 16 lanes of a row group then read 8 banks, and the four row groups
-// of a wavefront, 4 tokens apart, land 16 banks apart: no conflicts.
-constexpr int kVtRowBytes = kD * 2 + 16;
-constexpr int kVtWaveBytes = SPEC_BLOCK_SIZE * kVtRowBytes;
+// are padded by 16 bytes (272 at D = 128): the 16 lanes of a row group then read 8 banks, and the
+// four row groups of a wavefront, 4 tokens apart, land 16 banks apart: no conflicts.
+constexpr int vt_row_bytes(int D) { return D * 2 + 16; }
+constexpr int vt_wave_bytes(int D) { return SPEC_BLOCK_SIZE * vt_row_bytes(D); }
 
 template <int NT, int WG, bool TM = false, int D = kD>
 struct AttnShared {
@@ -980,7 +980,7 @@ struct AttnShared {
     float m[2][NT][kWave];
     float l[2][NT][kWave];
     int last;
-    alignas(16) unsigned char vt[TM ? kWaves * kVtWaveBytes : 16];   // token-major pages: V staged per wavefront
+    alignas(16) unsigned char vt[TM ? kWaves * vt_wave_bytes(D) : 16];   // token-major pages: V staged per wavefront
 };
 
 // The order in which the attention items take the requests (longest first), as the kernel
@@ -996,15 +996,16 @@ struct OrderTable {
 // VAR: 0 = pages in the matrix-operand layout, softmax weights fed as bf16 high + low parts;
 //      1 = the same with the weights as one bf16 (an experiment switch);
 //      2 = token-major pages (V transposed through LDS), weights as high + low parts;
-//      3 = as 0 with a head dim of 64 (all others: 128).
-constexpr int head_dim_of(int VAR) { return VAR == 3 ? 64 : kD; }
+//      3 = as 0 with a head dim of 64, 4 = as 2 with a head dim of 64 (all others: 128).
+constexpr int head_dim_of(int VAR) { return (VAR == 3 || VAR == 4) ? 64 : kD; }
+constexpr bool token_major_of(int VAR) { return VAR == 2 || VAR == 4; }
 
 template <int NT, int WG, int VAR>
 __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order, int item,
-                                          AttnShared<NT, WG, VAR == 2, head_dim_of(VAR)> &sh)
+                                          AttnShared<NT, WG, token_major_of(VAR), head_dim_of(VAR)> &sh)
 {
     constexpr bool SPLIT_P = VAR != 1;
-    constexpr bool TM = VAR == 2;
+    constexpr bool TM = token_major_of(VAR);
     constexpr int D = head_dim_of(VAR);
     constexpr int KK = D / 32;                        // 32-dim steps of the score product = 1 KB loads per K or V page
     constexpr int MT = D / 16;                        // 16-dim slices of the output
@@ -1012,7 +1013,7 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
     constexpr int kPageHeadBytes = SPEC_BLOCK_SIZE * D * 2;   // one (page, KV head) of K or of V: 4096 at D = 128
     constexpr int QP = D / 8;                         // 16-byte pieces of a bf16 query row
     constexpr int QI = (NT * WG * 16 * QP + kThreads - 1) / kThreads;   // ... of all the block's rows, per thread
-    static_assert(!TM || D == kD, "token-major pages: head dim 128 only");
+    constexpr int kVtRowBytes = vt_row_bytes(D), kVtWaveBytes = vt_wave_bytes(D);
     constexpr int PW = kWaves / WG;   // wavefronts that share the pages of a group between them
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -1127,7 +1128,7 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
         const __amdgpu_buffer_rsrc_t vd = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<char *>(vhead + (size_t)page * page_stride), 0, bytes, kBufferFlags);
         if constexpr (TM) {
-            // K: token n16, dims 32 i + 8 g .. + 7 sit at n16 * 256 + 64 i + 16 g
+            // K: token n16, dims 32 i + 8 g .. + 7 sit at n16 * 2 D + 64 i + 16 g
 #pragma unroll
             for (int i = 0; i < KK; ++i)
                 r.k[i] = __builtin_amdgcn_raw_buffer_load_b128(kd, n16 * (D * 2) + g * 16, i * 64, kStreamPolicy);
@@ -1163,15 +1164,16 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
             // V through this wavefront's LDS region: rows in, operand order out (LDS executes a
             // wavefront's accesses in order, so the reads see the writes without a barrier)
             unsigned char *vl = sh.vt + wave * kVtWaveBytes;
+            constexpr int LR = D / 8;   // lanes per token row of a 1 KB load (16 bytes each)
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-                *reinterpret_cast<u32x4 *>(vl + (4 * i + (lane >> 4)) * kVtRowBytes + (lane & 15) * 16) = cur.v[i];
+            for (int i = 0; i < KK; ++i)
+                *reinterpret_cast<u32x4 *>(vl + ((kWave / LR) * i + lane / LR) * kVtRowBytes + (lane % LR) * 16) = cur.v[i];
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             const unsigned char *src = vl + (4 * g) * kVtRowBytes + n16 * 2;
 #pragma unroll
-            for (int pp = 0; pp < 4; ++pp) {
+            for (int pp = 0; pp < KK; ++pp) {
                 uint32_t w[4];
 #pragma unroll
                 for (int hf = 0; hf < 2; ++hf) {
@@ -1581,7 +1583,7 @@ __global__ __launch_bounds__(kThreads, 2) void spec_step_kernel(StepArgs args)
         }
     }
     if constexpr (HAS_ATTN) {
-        __shared__ AttnShared<NT, WG, VAR == 2, head_dim_of(VAR)> ash;
+        __shared__ AttnShared<NT, WG, token_major_of(VAR), head_dim_of(VAR)> ash;
         OrderTable order;
         order.n = args.order.n;
         order.pairs = (uniform_u32_ptr)((const char __attribute__((address_space(4))) *)__builtin_amdgcn_kernarg_segment_ptr() +
@@ -1646,7 +1648,8 @@ hipError_t launch(const AttnParams &ap, const RejectParams &rp, int n_stat, int 
         return hipGetLastError();
     };
     if constexpr (HAS_ATTN) {
-        if (ap.kv_layout == SPEC_KV_TOKEN_MAJOR) return go(std::integral_constant<int, 2>());
+        if (ap.kv_layout == SPEC_KV_TOKEN_MAJOR)
+            return ap.d == 64 ? go(std::integral_constant<int, 4>()) : go(std::integral_constant<int, 2>());
         if (ap.d == 64) return go(std::integral_constant<int, 3>());
         // (the single-bf16 experiment exists for one wave group only)
         if constexpr (WG == 1)
@@ -1730,7 +1733,7 @@ hipError_t launch_step_fused(const AttnParams *attn, int row_tiles, const Reject
         const bool shape_ok = (ap.row_groups == 1 && row_tiles >= 1 && row_tiles <= 3) ||
                               ((ap.row_groups == 2 || ap.row_groups == 4) && (row_tiles == 2 || row_tiles == 3));
         // (a wavefront keeps the block-table entries of its pages one per lane)
-        const bool dim_ok = ap.d == kD || (ap.d == 64 && ap.kv_layout == SPEC_KV_MFMA);
+        const bool dim_ok = ap.d == kD || ap.d == 64;
         if (!dim_ok || !shape_ok || ap.chunk_tokens > 4096 / ap.row_groups || ap.chunk_tokens % SPEC_BLOCK_SIZE != 0 ||
             ap.capacity_tokens > ap.chunk_tokens * ap.max_chunks ||
             (ap.fused_combine && ap.max_chunks > kMaxFusedChunks) || (order != nullptr && order->n != 0 && order->n != ap.B))

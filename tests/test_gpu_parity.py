@@ -191,6 +191,24 @@ def test_token_major_pages_on_the_matrix_path(harness, name, kw, tiles):
     print("%s token-major: attn err %.2e" % (name, err))
 
 
+@pytest.mark.parametrize("layout", [sv.KV_TOKEN_MAJOR, sv.KV_MFMA], ids=["token_major", "tiles"])
+@pytest.mark.parametrize("name", ["gqa8_k2", "d64", "many_rows"])
+def test_bf16_on_the_generic_kernels(harness, tuning, name, layout):
+    """The scalar kernels read bf16 pages in both layouts too (the planner takes them for fp32 only; the
+    switch forces them): unsplit and split requests, the whole step."""
+    print("case forced generic", name, "layout", layout, flush=True)
+    tuning("SPEC_VERIFY_FORCE_GENERIC", 1)
+    kw = dict(SMALL)[name]
+    w = W.make_workload(name, V=64, dtype="bf16", draft_std=2.0, sigma=1.0, data_seed=zlib.crc32(name.encode()) % 1000,
+                        philox_seed=3, **kw)
+    ds = harness.DeviceStep(w, kv_layout=layout)
+    assert ds.plan()["attn_path"] == sv.PATH_GENERIC
+    ds.run_step()
+    res = ds.results()
+    check_attn(w, res["out"])
+    check_reject(w, res)
+
+
 D64_CASES = [
     # name, kwargs, row tiles, tuning switch
     ("d64_mha", dict(B=3, Hq=4, Hkv=4, d=64, kv_len=[37, 16, 300], k=[3, 0, 8]), 1, None),
@@ -203,16 +221,17 @@ D64_CASES = [
 ]
 
 
+@pytest.mark.parametrize("layout", [sv.KV_MFMA, sv.KV_TOKEN_MAJOR], ids=["tiles", "token_major"])
 @pytest.mark.parametrize("name,kw,tiles,switch", D64_CASES, ids=[c[0] for c in D64_CASES])
-def test_head_dim_64_on_the_matrix_path(harness, tuning, name, kw, tiles, switch):
-    """bf16 with a head dim of 64 in the matrix-operand page layout: half the matrix instructions per page,
-    2 KB per (page, KV head); unsplit, split with the in-kernel merge, and split with the merge launch."""
-    print("case head dim 64", name, flush=True)
+def test_head_dim_64_on_the_matrix_path(harness, tuning, name, kw, tiles, switch, layout):
+    """bf16 with a head dim of 64, in both page layouts: half the matrix instructions per page, 2 KB per
+    (page, KV head); unsplit, split with the in-kernel merge, split with the merge launch, wave groups."""
+    print("case head dim 64", name, "layout", layout, flush=True)
     if switch:
         tuning(*switch)
     w = W.make_workload(name, V=64, dtype="bf16", draft_std=2.0, sigma=1.0, data_seed=zlib.crc32(name.encode()) % 1000,
                         philox_seed=3, **kw)
-    ds = harness.DeviceStep(w, kv_layout=sv.KV_MFMA)
+    ds = harness.DeviceStep(w, kv_layout=layout)
     plan = ds.plan()
     assert plan["attn_path"] == sv.PATH_MFMA and plan["row_tiles"] == tiles, plan
     assert plan["row_groups"] == {"d64_two_groups": 2, "d64_four_groups": 4}.get(name, 1), plan

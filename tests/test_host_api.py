@@ -338,7 +338,7 @@ def test_every_supported_row_count_takes_the_matrix_path(Hq, Hkv, k, path, tiles
     assert (info["attn_path"], info["row_tiles"], info["row_groups"]) == (path, tiles, groups), info
     assert info["launches"] == 1
     # token-major bf16 pages take the same path with the same split of the rows (V transposed through LDS);
-    # fp32 takes the generic kernels; d = 64 takes the matrix path in the tiled layout
+    # fp32 takes the generic kernels; d = 64 takes the matrix path like d = 128
     tm = sv.spec_verify_plan(_attn(B=B, Hq=Hq, Hkv=Hkv, kv_len=(300,) * B, q_len=(k + 1,) * B, max_blocks=32,
                                    layout=sv.KV_TOKEN_MAJOR), None)
     assert (tm["attn_path"], tm["row_tiles"], tm["row_groups"], tm["launches"]) == (path, tiles, groups, 1), tm
@@ -346,8 +346,9 @@ def test_every_supported_row_count_takes_the_matrix_path(Hq, Hkv, k, path, tiles
                                      dtype=sv.SPEC_F32, layout=sv.KV_TOKEN_MAJOR), None)["attn_path"] == sv.PATH_GENERIC
     d64 = sv.spec_verify_plan(_attn(B=B, Hq=Hq, Hkv=Hkv, d=64, kv_len=(300,) * B, q_len=(k + 1,) * B, max_blocks=32), None)
     assert (d64["attn_path"], d64["row_tiles"], d64["row_groups"]) == (path, tiles, groups), d64
-    assert sv.spec_verify_plan(_attn(B=B, Hq=Hq, Hkv=Hkv, d=64, kv_len=(300,) * B, q_len=(k + 1,) * B, max_blocks=32,
-                                     layout=sv.KV_TOKEN_MAJOR), None)["attn_path"] == sv.PATH_GENERIC
+    d64tm = sv.spec_verify_plan(_attn(B=B, Hq=Hq, Hkv=Hkv, d=64, kv_len=(300,) * B, q_len=(k + 1,) * B, max_blocks=32,
+                                      layout=sv.KV_TOKEN_MAJOR), None)
+    assert (d64tm["attn_path"], d64tm["row_tiles"], d64tm["row_groups"]) == (path, tiles, groups), d64tm
 
 
 def test_tuning_switches_are_read_once_and_on_reload(monkeypatch):
