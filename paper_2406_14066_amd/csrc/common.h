@@ -143,6 +143,12 @@ struct LaunchEvents {
 // matrix-instruction path (bf16, SPEC_KV_MFMA, d = 128; row_tiles tiles per wave group, ap.row_groups
 // wave groups per block).  `order` may be null.
 int step_attn_items(const AttnParams &ap);   // attention blocks of the launch
+// attention items per chunk index: one per (request, KV head), padded to whole rows of 8 blocks (one per XCD) when requests are split
+__host__ __device__ inline int attn_row_items(const AttnParams &ap)
+{
+    const int units = ap.B * ap.Hkv;
+    return ap.max_chunks > 1 ? (units + 7) / 8 * 8 : units;
+}
 hipError_t launch_step_fused(const AttnParams *attn, int row_tiles, const RejectParams *reject, const UnitOrder *order,
                              LaunchEvents events, hipStream_t stream);
 

@@ -1027,10 +1027,17 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
     // gets the same mix of chunk indices; the chunk indices that only the longest requests
     // have come last (blocks of the others for these indices exit at once), instead of
     // always falling on the same XCDs.
+    // With split requests a row of items (one chunk index) is padded to whole rows of kXcds blocks, so
+    // that all chunks of a (request, KV head) run on one XCD and find its query rows, table entries,
+    // partial results and ticket in that XCD's L2 (spread over the XCDs the ragged long-context
+    // workload takes 4% longer).
     const int n_units = p.B * p.Hkv;
-    const int chunk = item / n_units;
-    const int kvh = (item % n_units) % p.Hkv;
-    int b = (item % n_units) / p.Hkv;   // rank in the order of the attention items
+    const int row_items = attn_row_items(p);
+    const int chunk = item / row_items;
+    const int place = item - chunk * row_items;
+    if (place >= n_units) return;   // padding
+    const int kvh = place % p.Hkv;
+    int b = place / p.Hkv;   // rank in the order of the attention items
     if (order.n > 0) {
         const uint32_t pair = order.pairs[b >> 1];
         b = (int)((b & 1) ? pair >> 16 : pair & 0xFFFFu);
@@ -1710,7 +1717,7 @@ SPEC_STEP_DEFINE(launch_step_tiles3_groups4, 3, 4)
 #if SPEC_STEP_HAS_PART(0)
 int step_attn_items(const AttnParams &ap)
 {
-    return ap.B * ap.Hkv * ap.max_chunks;
+    return attn_row_items(ap) * ap.max_chunks;
 }
 
 hipError_t launch_step_fused(const AttnParams *attn, int row_tiles, const RejectParams *reject, const UnitOrder *order,
