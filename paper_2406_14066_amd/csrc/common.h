@@ -140,8 +140,8 @@ struct LaunchEvents {
 };
 
 // One launch for the whole step (either half may be absent).  `attn` needs the
-// matrix-instruction path (bf16, SPEC_KV_MFMA, d = 128; row_tiles tiles per wave group, ap.row_groups
-// wave groups per block).  `order` may be null.
+// matrix-instruction path (bf16, either page layout, d = 128 or 64; row_tiles tiles per wave
+// group, ap.row_groups wave groups per block).  `order` may be null.
 int step_attn_items(const AttnParams &ap);   // attention blocks of the launch
 // attention items per chunk index: one per (request, KV head), padded to whole rows of 8 blocks (one per XCD) when requests are split
 __host__ __device__ inline int attn_row_items(const AttnParams &ap)
