@@ -66,7 +66,7 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
-constexpr int kD = 128;   // head dim of the main variants (one for 64 exists for pages in the matrix-operand layout)
+constexpr int kD = 128;   // head dim of the main variants (those for 64: see head_dim_of)
 constexpr int kBufferFlags = 0x00020000;   // raw 32-bit buffer descriptor, word 3
 // Cache policy of the loads that stream data read once (KV pages, the race's logit rows):
 // non-temporal, i.e. the lines are first in line for replacement in the L2.  Without it the
@@ -1143,7 +1143,8 @@ __device__ __forceinline__ void attn_role(const AttnParams &p, OrderTable order,
 #pragma unroll
             for (int i = 0; i < KK; ++i) r.k[i] = __builtin_amdgcn_raw_buffer_load_b128(kd, lane_off, i * 1024, kStreamPolicy);
         }
-        // V: in operand order already, or (token-major) as whole rows: lane L holds token 4 i + L / 16, dims 8 (L % 16) .. + 7
+        // V: in operand order already, or (token-major) as whole rows: with D / 8 lanes per row, lane L of load i holds
+        // token (512 / D) i + 8 L / D, dims 8 (L % (D / 8)) .. + 7
 #pragma unroll
         for (int i = 0; i < KK; ++i) r.v[i] = __builtin_amdgcn_raw_buffer_load_b128(vd, lane_off, i * 1024, kStreamPolicy);
     };
