@@ -382,6 +382,17 @@ def test_small_launches_are_split_sparingly(B, Hq, Hkv, length, most_chunks):
         assert plan["max_chunks"] > 8 and plan["chunk_tokens"] >= 1024, plan
 
 
+def test_split_requests_get_whole_rows_of_eight_attention_items():
+    """With split requests every chunk index has its items padded to whole rows of 8 blocks (one per XCD),
+    so that all chunks of a (request, KV head) run on the same XCD; unsplit requests need no padding."""
+    long = _attn(B=3, Hq=32, Hkv=4, kv_len=(20000, 17000, 23000), q_len=(5, 5, 5), max_blocks=1500)
+    plan = sv.spec_verify_plan(long, None)
+    assert plan["max_chunks"] > 1 and plan["attn_blocks"] == 16 * plan["max_chunks"], plan      # 12 units -> 16 items per row
+    short = _attn(B=3, Hq=32, Hkv=4, kv_len=(200, 170, 230), q_len=(5, 5, 5), max_blocks=16)
+    plan = sv.spec_verify_plan(short, None)
+    assert plan["max_chunks"] == 1 and plan["attn_blocks"] == 12, plan
+
+
 def test_plan_is_reused_for_an_unchanged_shape_and_follows_a_changed_one():
     q_len = (3,) * 6
     a = _attn(B=6, Hq=8, Hkv=2, kv_len=(100, 200, 300, 400, 500, 600), q_len=q_len, max_blocks=64)
